@@ -1,0 +1,270 @@
+"""CPU checker ("oracle") for the selective-rollout decode path -- TEST INFRASTRUCTURE ONLY.
+
+A plain, slow evaluation of what the GPU path computes, written from the paper's
+definitions (Section 3.2 for the signal d_K, Eq. 2 for the gate, Eq. 1 for the
+advantage, Appendix C.1 for the gated rollout loop) and from the textbook
+definition of a pre-norm GQA/SwiGLU decoder.  It shares no code with the GPU
+library and must never be imported by it.  Only tests, the smoke check and the
+benchmark's CPU-baseline leg may use it.
+
+The arithmetic lives in sr_oracle.c (double precision; a float build is available
+as `load(real="float")`); this module is the ctypes wrapper plus the episode loop.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "sr_oracle.c")
+_LIBS: dict = {}
+
+
+def build(force: bool = False) -> None:
+    for real in ("double", "float"):
+        out = os.path.join(_HERE, f"libsroracle_{real}.so")
+        if force or not os.path.exists(out) or os.path.getmtime(out) < os.path.getmtime(_SRC):
+            subprocess.check_call(["gcc", "-O3", "-march=native", "-fopenmp", "-fPIC", "-shared", "-std=c11",
+                                   f"-DSRO_REAL={real}", "-o", out, _SRC, "-lm"])
+
+
+class _Shape(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim", "ffn", "vocab", "qkv_bias")] + \
+               [("rms_eps", ctypes.c_double), ("rope_theta", ctypes.c_double)]
+
+
+def load(real: str = "double"):
+    if real not in _LIBS:
+        build()
+        L = ctypes.CDLL(os.path.join(_HERE, f"libsroracle_{real}.so"))
+        vp, ci, cd = ctypes.c_void_p, ctypes.c_int, ctypes.c_double
+        L.sro_lev.restype = ci
+        L.sro_lev.argtypes = [vp, ci, vp, ci]
+        L.sro_pair_sum.restype = ctypes.c_int64
+        L.sro_pair_sum.argtypes = [vp, ci, ci, ci]
+        L.sro_gate_bound.restype = ctypes.c_int64
+        L.sro_gate_bound.argtypes = [cd, ci, ci]
+        L.sro_mean_prefix_distance.restype = cd
+        L.sro_mean_prefix_distance.argtypes = [vp, ci, ci, ci]
+        L.sro_gate_batch.restype = None
+        L.sro_gate_batch.argtypes = [vp, ci, ci, ci, vp, ci, cd, vp, vp]
+        L.sro_advantage.restype = None
+        L.sro_advantage.argtypes = [vp, ci, cd, vp]
+        L.sro_model_new.restype = vp
+        L.sro_model_new.argtypes = [ctypes.POINTER(_Shape), vp, vp, vp]
+        L.sro_model_set_layer.restype = None
+        L.sro_model_set_layer.argtypes = [vp, ci] + [vp] * 12
+        L.sro_model_free.restype = None
+        L.sro_model_free.argtypes = [vp]
+        L.sro_seq_new.restype = vp
+        L.sro_seq_new.argtypes = [vp, ci]
+        L.sro_seq_free.restype = None
+        L.sro_seq_free.argtypes = [vp]
+        L.sro_seq_len.restype = ci
+        L.sro_seq_len.argtypes = [vp]
+        L.sro_seq_truncate.restype = None
+        L.sro_seq_truncate.argtypes = [vp, ci]
+        L.sro_forward_token.restype = ci
+        L.sro_forward_token.argtypes = [vp, vp, ctypes.c_int32, vp]
+        L.sro_forward.restype = ci
+        L.sro_forward.argtypes = [vp, vp, vp, ci, vp]
+        L.sro_argmax.restype = ci
+        L.sro_argmax.argtypes = [vp, ci, ctypes.POINTER(cd)]
+        L.sro_real_bytes.restype = ci
+        L.sro_rope_apply.restype = None
+        L.sro_rope_apply.argtypes = [vp, ci, ci, cd]
+        _LIBS[real] = L
+    return _LIBS[real]
+
+
+# ----------------------------------------------------------------------------
+# gate
+# ----------------------------------------------------------------------------
+def _i32(a):
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def lev(a, b) -> int:
+    a, b = _i32(a), _i32(b)
+    return load().sro_lev(a.ctypes.data, len(a), b.ctypes.data, len(b))
+
+
+def pair_sum(actions, K: int) -> int:
+    """S_K for one group; actions is [G, >=K]."""
+    a = _i32(actions)
+    return int(load().sro_pair_sum(a.ctypes.data, a.shape[0], a.shape[1], K))
+
+
+def gate_bound(d_L: float, G: int, K: int) -> int:
+    """Smallest integer T with: d_K < d_L  <=>  S_K < T  (Eq. 2 in integers)."""
+    return int(load().sro_gate_bound(d_L, G, K))
+
+
+def mean_prefix_distance(actions, K: int) -> float:
+    a = _i32(actions)
+    return float(load().sro_mean_prefix_distance(a.ctypes.data, a.shape[0], a.shape[1], K))
+
+
+def gate_batch(actions, lens, d_L: float):
+    """actions [n_groups, G, stride] -> (sums int32 [n_lens, n_groups], cut uint8 [n_lens, n_groups])."""
+    a = _i32(actions)
+    n_groups, G, stride = a.shape
+    lens = _i32(lens)
+    sums = np.zeros((len(lens), n_groups), dtype=np.int32)
+    cut = np.zeros((len(lens), n_groups), dtype=np.uint8)
+    load().sro_gate_batch(a.ctypes.data, n_groups, G, stride, lens.ctypes.data, len(lens), d_L,
+                          sums.ctypes.data, cut.ctypes.data)
+    return sums, cut
+
+
+def advantage(r, eps: float = 1e-6) -> np.ndarray:
+    r = np.ascontiguousarray(r, dtype=np.float64)
+    A = np.empty_like(r)
+    load().sro_advantage(r.ctypes.data, len(r), eps, A.ctypes.data)
+    return A
+
+
+# ----------------------------------------------------------------------------
+# decoder
+# ----------------------------------------------------------------------------
+class Model:
+    """Borrowed bf16 weights (uint16 numpy arrays, kept alive here) behind the C decoder."""
+
+    def __init__(self, weights, real: str = "double", n_layers: int | None = None):
+        self.L = load(real)
+        self.real = np.float64 if real == "double" else np.float32
+        self.w = weights
+        s = weights.shape
+        nl = len(weights.layers) if n_layers is None else n_layers
+        self.shape = s
+        self.n_layers = nl
+        sh = _Shape(nl, s.hidden, s.n_q_heads, s.n_kv_heads, s.head_dim, s.ffn, s.vocab, int(s.qkv_bias),
+                    s.rms_eps, s.rope_theta)
+        self.h = self.L.sro_model_new(ctypes.byref(sh), weights.embed.ctypes.data, weights.lm_head.ctypes.data,
+                                      weights.final_norm.ctypes.data)
+        order = ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "bq", "bk", "bv", "norm1", "norm2")
+        for l in range(nl):
+            d = weights.layers[l]
+            self.L.sro_model_set_layer(self.h, l, *[d[k].ctypes.data for k in order])
+
+    def __del__(self):
+        try:
+            self.L.sro_model_free(self.h)
+        except Exception:
+            pass
+
+    def new_seq(self, cap: int) -> "Seq":
+        return Seq(self, cap)
+
+
+class Seq:
+    def __init__(self, model: Model, cap: int):
+        self.m = model
+        self.h = model.L.sro_seq_new(model.h, cap)
+
+    def __del__(self):
+        try:
+            self.m.L.sro_seq_free(self.h)
+        except Exception:
+            pass
+
+    def __len__(self):
+        return self.m.L.sro_seq_len(self.h)
+
+    def truncate(self, n: int):
+        self.m.L.sro_seq_truncate(self.h, n)
+
+    def forward(self, tokens, want_logits: bool = True):
+        """Append tokens; returns the logits after the last one (or None)."""
+        t = _i32(np.atleast_1d(tokens))
+        out = np.empty(self.m.shape.vocab, dtype=self.m.real) if want_logits else None
+        rc = self.m.L.sro_forward(self.m.h, self.h, t.ctypes.data, len(t),
+                                  out.ctypes.data if want_logits else None)
+        if rc:
+            raise RuntimeError("oracle sequence capacity exceeded")
+        return out
+
+
+def rope_apply(vec, pos: int, theta: float) -> np.ndarray:
+    """Rotate one head vector (fp64) to absolute position pos."""
+    v = np.array(vec, dtype=np.float64)
+    load().sro_rope_apply(v.ctypes.data, len(v), pos, theta)
+    return v
+
+
+def argmax(logits):
+    """(lowest index among maxima, gap between the best and second-best logit)."""
+    lg = np.ascontiguousarray(logits)
+    L = load("double" if lg.dtype == np.float64 else "float")
+    gap = ctypes.c_double()
+    idx = L.sro_argmax(lg.ctypes.data, len(lg), ctypes.byref(gap))
+    return idx, gap.value
+
+
+# ----------------------------------------------------------------------------
+# gated group rollout (Appendix C.1), greedy decoding
+# ----------------------------------------------------------------------------
+def run_episode(model: Model, prompts, obs_fn, G: int, turns: int, act_len: int, action_mod: int,
+                gate_turns, d_L: float, keep_logits: bool = False):
+    """Rolls every group forward turn by turn, gating at the given turns.
+
+    prompts: int32 [n_groups, P] (shared by the G members of a group).
+    obs_fn(turn) -> int32 [n_groups*G, obs_len] rows in ORIGINAL (group-major) order.
+    Each turn appends the observation chunk, then decodes act_len tokens greedily; the
+    turn's action id is (first decoded token) mod action_mod.  After a gate turn K the
+    pairwise-distance sum S_K over the first K actions is compared with gate_bound and
+    groups with S_K < bound stop there and leave the batch.
+
+    Returns a dict of per-turn records, all indexed by original sequence / group ids.
+    """
+    prompts = _i32(prompts)
+    n_groups, P = prompts.shape
+    n_seq = n_groups * G
+    obs0 = obs_fn(0)
+    cap = P + turns * (obs0.shape[1] + act_len)
+    seqs = [model.new_seq(cap) for _ in range(n_seq)]
+    live = list(range(n_groups))
+    actions = np.full((n_seq, turns), -1, dtype=np.int32)
+    rec = {"tokens": [], "gaps": [], "logits": [], "live_groups": [], "gate": {}, "decoded_tokens": 0}
+
+    logits = [None] * n_seq
+    for g in live:
+        for m in range(G):
+            logits[g * G + m] = seqs[g * G + m].forward(prompts[g])
+
+    for turn in range(turns):
+        obs = obs0 if turn == 0 else obs_fn(turn)
+        rows = [g * G + m for g in live for m in range(G)]
+        rec["live_groups"].append(list(live))
+        for r in rows:
+            logits[r] = seqs[r].forward(obs[r])
+        t_tok = np.full((act_len, n_seq), -1, dtype=np.int32)
+        t_gap = np.full((act_len, n_seq), np.inf)
+        t_log = []
+        for a in range(act_len):
+            if keep_logits:
+                t_log.append({r: logits[r].copy() for r in rows})
+            for r in rows:
+                tok, gap = argmax(logits[r])
+                t_tok[a, r], t_gap[a, r] = tok, gap
+                if a == 0:
+                    actions[r, turn] = tok % action_mod
+                logits[r] = seqs[r].forward([tok])
+                rec["decoded_tokens"] += 1
+        rec["tokens"].append(t_tok)
+        rec["gaps"].append(t_gap)
+        rec["logits"].append(t_log)
+        K = turn + 1
+        if K in gate_turns:
+            bound = gate_bound(d_L, G, K)
+            sums = {g: pair_sum(actions[g * G:(g + 1) * G], K) for g in live}
+            cut = {g: sums[g] < bound for g in live}
+            rec["gate"][K] = {"bound": bound, "sums": sums, "cut": cut}
+            live = [g for g in live if not cut[g]]
+    rec["actions"] = actions
+    rec["final_live_groups"] = live
+    return rec
