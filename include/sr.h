@@ -1,0 +1,197 @@
+/*
+ * sr.h -- C boundary of the selective-rollout decode library for AMD MI355X (gfx950).
+ *
+ * The library runs the group-batched multi-turn rollout of one GRPO step and the
+ * Selective-Rollout gate that retires converged groups mid-batch:
+ *
+ *   - G samples per prompt ("group") advance one environment step ("turn") at a time;
+ *     each turn an observation chunk is appended to every live sequence and an action
+ *     is decoded token by token (paper Section 2.2 and Appendix C.1/C.2: token layout
+ *     [prompt, o_1, a_1, o_2, a_2, ...], one model call per step per trajectory);
+ *   - after turn K the mean pairwise prefix edit distance d_K of each group's action
+ *     sequences (Section 3.2) is compared with the threshold d_L and a group is cut iff
+ *     d_K < d_L (Eq. 2); a cut group stops generating and leaves the batch (Section 3.2,
+ *     Appendix C.1).
+ *
+ * Conventions
+ *   - Every function returns SR_OK (0) or a negative sr_status; nothing throws or exits.
+ *   - "device" pointers are HIP device memory of the current device; "host" pointers are
+ *     ordinary host memory.  The caller owns every buffer it passes in.  The library owns
+ *     its packed weight copy, the KV page pool, page tables, the action table and all
+ *     scratch; they are released by sr_destroy.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls are
+ *     asynchronous on that stream unless stated otherwise.  One context must be driven
+ *     from one stream at a time.
+ *   - Batch rows are ordered group-major: live row r belongs to live group r / G, member
+ *     r % G.  Retirement removes whole groups and keeps the order of the survivors.
+ *   - All live sequences have the same length at all times (lock-step turns).
+ *   - bf16 tensors are raw 16-bit patterns; matrices are row-major [out_features][in_features].
+ */
+#ifndef SR_H
+#define SR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SR_OK = 0,
+    SR_E_ARG = -1,    /* null pointer, bad shape, turn out of range, chunk_len <= 0, G < 2, ... */
+    SR_E_NOMEM = -2,  /* KV page pool exhausted (checked on the host before any launch) or allocation failed */
+    SR_E_STATE = -3,  /* call out of order: decode before prefill, gate with too few recorded actions, ... */
+    SR_E_HIP = -4     /* a HIP runtime call failed; sr_strerror gives the text */
+} sr_status;
+
+typedef struct sr_ctx sr_ctx;
+
+/* Decoder shape: pre-norm blocks, RMSNorm, rotate-half RoPE, grouped-query attention,
+ * SwiGLU FFN, untied LM head.  head_dim must be 64 or 128; n_q_heads % n_kv_heads == 0. */
+typedef struct {
+    int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
+    float rms_eps, rope_theta;
+    int32_t qkv_bias; /* 1: q/k/v projections add a bias vector */
+} sr_model_shape;
+
+typedef struct {
+    int32_t page_tokens;     /* tokens per KV page: 32, 64 or 128 */
+    int32_t max_seq_len;     /* longest context any sequence will reach */
+    int32_t max_turns;       /* width of the per-sequence action table */
+    int32_t action_mod;      /* action id of a turn = (first decoded token of the turn) % action_mod;
+                                0 = the host supplies action ids with sr_set_actions */
+    int32_t max_prefill_rows;/* rows (sequences x chunk tokens) processed per prefill pass; 0 = default 8192 */
+    uint64_t kv_pool_bytes;  /* size of the KV page pool (K and V, all layers) */
+} sr_options;
+
+/* bf16 device pointers; borrowed only for the duration of sr_load_weights. */
+typedef struct {
+    const void *wq, *wk, *wv;   /* [n_q*d][hidden], [n_kv*d][hidden], [n_kv*d][hidden] */
+    const void *wo;             /* [hidden][n_q*d] */
+    const void *wg, *wu;        /* [ffn][hidden] */
+    const void *wd;             /* [hidden][ffn] */
+    const void *bq, *bk, *bv;   /* [n_q*d], [n_kv*d], [n_kv*d]; ignored when qkv_bias == 0 */
+    const void *norm1, *norm2;  /* [hidden] RMSNorm gains before attention / before the FFN */
+} sr_layer_weights;
+
+typedef struct {
+    const void *embed;              /* [vocab][hidden] */
+    const void *lm_head;            /* [vocab][hidden] */
+    const void *final_norm;         /* [hidden] */
+    const sr_layer_weights *layers; /* HOST array of n_layers entries (of device pointers) */
+} sr_weights;
+
+typedef struct {
+    int64_t decoded_tokens;   /* tokens appended by sr_decode_step, summed over sequences */
+    int64_t prefill_tokens;   /* tokens appended by sr_prefill_chunk (shared prompt counted once per group) */
+    int32_t n_live_groups, n_live_seq, seq_len, turn;
+    int32_t pages_total, pages_in_use;
+    int32_t groups_retired;   /* total over all gates so far */
+    int32_t pages_freed;      /* total over all gates so far */
+    int32_t cow_page_copies;  /* pages duplicated because a member appended into a shared page */
+} sr_stats_t;
+
+/*
+ * Create a context for n_groups groups of G sequences each and threshold d_L
+ * (Eq. 2; resolved to the rational round(d_L*1e6)/1e6).  Allocates the KV pool and all
+ * scratch on the current device.  *out is set on success.
+ * SR_E_ARG: null pointers, G < 2, unsupported shape/options; SR_E_NOMEM / SR_E_HIP: allocation failed.
+ */
+int sr_init(sr_ctx **out, const sr_model_shape *shape, int n_groups, int G, double threshold,
+            const sr_options *opt);
+
+/* Release everything the context owns.  Synchronises the device.  NULL is allowed. */
+void sr_destroy(sr_ctx *ctx);
+
+/*
+ * Copy the weights into the library's own packed layout (device -> device, on `stream`)
+ * and wait for completion; the caller may free its tensors afterwards.
+ */
+int sr_load_weights(sr_ctx *ctx, const sr_weights *w, void *stream);
+
+/*
+ * Append chunk_len tokens to every live sequence and leave the logits that follow the
+ * last of them (Section 2.2: the environment's observation is appended before each action;
+ * Appendix C.2: observation tokens are injected, not generated).
+ *   shared_per_group = 1: tokens is device int32 [n_live_groups][chunk_len]; the chunk is the
+ *       prompt common to the G members of a group; its KV pages are computed once and
+ *       shared by the members (copy-on-write).  Only legal while every sequence is empty.
+ *   shared_per_group = 0: tokens is device int32 [n_live_seq][chunk_len], one chunk per
+ *       sequence; starts a new turn (the next sr_decode_step records the turn's action).
+ * SR_E_ARG: bad arguments or max_seq_len exceeded; SR_E_NOMEM: not enough free KV pages
+ * (nothing is launched); SR_E_STATE: shared prefill on non-empty sequences, weights not loaded.
+ * With no live group the call is a no-op returning SR_OK.
+ */
+int sr_prefill_chunk(sr_ctx *ctx, const int32_t *tokens, int chunk_len, int shared_per_group,
+                     void *stream);
+
+/*
+ * Decode one token for every live sequence: pick token = forced[r] if forced != NULL, else
+ * the greedy choice (largest current logit, lowest index on ties); append it and compute
+ * the logits that follow it.  out_tokens (device int32 [n_live_seq], may be NULL) always
+ * receives the greedy choice, also under forcing.  On the first decode step after a
+ * per-sequence prefill the turn's action id (token % action_mod, from the token actually
+ * appended) is recorded in the action table.
+ * SR_E_STATE before any prefill; SR_E_ARG when max_seq_len would be exceeded; SR_E_NOMEM
+ * when a needed KV page cannot be allocated.
+ */
+int sr_decode_step(sr_ctx *ctx, const int32_t *forced, int32_t *out_tokens, void *stream);
+
+/*
+ * Evaluate the gate after turn K = `turn` (1-based count of recorded actions compared):
+ * for each live group S_K = sum over the G(G-1)/2 member pairs of the Levenshtein distance
+ * between their first K action ids (Section 3.2; all members hold K actions, so
+ * d_K = S_K / (C(G,2)*K)), and retire = [d_K < d_L] (Eq. 2, strict) evaluated in integers as
+ * S_K < ceil(round(d_L*1e6) * C(G,2) * K / 1e6).
+ * out_sums (device int32 [n_live_groups]) and out_retire (device uint8 [n_live_groups]) may
+ * be NULL; the mask is also kept inside the context for sr_retire_and_compact.
+ * SR_E_ARG: turn < 1 or > max_turns; SR_E_STATE: fewer than `turn` actions recorded.
+ */
+int sr_gate(sr_ctx *ctx, int turn, int32_t *out_sums, uint8_t *out_retire, void *stream);
+
+/*
+ * Apply the mask of the preceding sr_gate: rows of retired groups are removed from every
+ * per-sequence array (order of survivors kept), their KV pages are released (a shared
+ * prompt page returns to the pool when its last holder leaves) and the batch shrinks.
+ * This call waits for the mask on the host (the one synchronisation per gate turn) and
+ * stores the number of surviving groups in *host_n_live_groups (may be NULL).
+ * Retiring every group is legal; later prefill/decode calls are then no-ops.
+ * SR_E_STATE: no gate since the last compaction.
+ */
+int sr_retire_and_compact(sr_ctx *ctx, int *host_n_live_groups, void *stream);
+
+/*
+ * Stand-alone gate over many groups and several prefix lengths (no context needed).
+ * actions: device int32 [n_groups][G][stride]; prefix_lens: HOST int [n_lens], each in
+ * [1, min(stride, 32)]; sums: device int32 [n_lens][n_groups]; retire: device uint8
+ * [n_lens][n_groups] (either may be NULL).  2 <= G <= 16, n_lens <= 8.
+ */
+int sr_gate_batch(const int32_t *actions, int n_groups, int G, int stride, const int *prefix_lens,
+                  int n_lens, double threshold, int32_t *sums, uint8_t *retire, void *stream);
+
+/* Overwrite the action ids of turn `turn` (1-based) for all live sequences:
+ * ids is device int32 [n_live_seq].  For action_mod == 0, or for tests. */
+int sr_set_actions(sr_ctx *ctx, int turn, const int32_t *ids, void *stream);
+
+/* Copy the action table of the live sequences: dst is device int32 [n_live_seq][max_turns];
+ * turns not yet recorded hold -1. */
+int sr_get_actions(sr_ctx *ctx, int32_t *dst, void *stream);
+
+/* Copy the current logits: dst is device float [n_live_seq][vocab]. */
+int sr_get_logits(sr_ctx *ctx, float *dst, void *stream);
+
+/* Original sequence index (group*G + member at sr_init time) of every live row:
+ * host int32 [n_live_seq].  Host-side bookkeeping only; does not touch the stream. */
+int sr_get_live_map(sr_ctx *ctx, int32_t *host_orig_seq_ids);
+
+/* Counters (host struct). */
+int sr_stats(sr_ctx *ctx, sr_stats_t *host_stats);
+
+/* Text for a status code; for SR_E_HIP the text of the last HIP error seen by this thread. */
+const char *sr_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SR_H */

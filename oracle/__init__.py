@@ -23,9 +23,28 @@ _SRC = os.path.join(_HERE, "sr_oracle.c")
 _LIBS: dict = {}
 
 
+def _cpu_tag() -> str:
+    """Short tag of this host's instruction-set flags: the library is built with -march=native, so a
+    copy built on another machine must not be loaded here."""
+    import hashlib
+    flags = ""
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("flags"):
+                flags = line
+                break
+    except OSError:
+        pass
+    return hashlib.sha1(flags.encode()).hexdigest()[:8]
+
+
+def _lib_path(real: str) -> str:
+    return os.path.join(_HERE, f"libsroracle_{real}_{_cpu_tag()}.so")
+
+
 def build(force: bool = False) -> None:
     for real in ("double", "float"):
-        out = os.path.join(_HERE, f"libsroracle_{real}.so")
+        out = _lib_path(real)
         if force or not os.path.exists(out) or os.path.getmtime(out) < os.path.getmtime(_SRC):
             subprocess.check_call(["gcc", "-O3", "-march=native", "-fopenmp", "-fPIC", "-shared", "-std=c11",
                                    f"-DSRO_REAL={real}", "-o", out, _SRC, "-lm"])
@@ -40,7 +59,7 @@ class _Shape(ctypes.Structure):
 def load(real: str = "double"):
     if real not in _LIBS:
         build()
-        L = ctypes.CDLL(os.path.join(_HERE, f"libsroracle_{real}.so"))
+        L = ctypes.CDLL(_lib_path(real))
         vp, ci, cd = ctypes.c_void_p, ctypes.c_int, ctypes.c_double
         L.sro_lev.restype = ci
         L.sro_lev.argtypes = [vp, ci, vp, ci]

@@ -1,0 +1,193 @@
+"""Selective-rollout decode for MI355X: thin ctypes binding over libsr.so (see include/sr.h).
+
+Argument marshalling only -- every step of the path runs in the library's HIP kernels.  PyTorch
+is used by callers for device memory and streams; this module never computes anything itself and
+there is no CPU fallback: if libsr.so is missing and cannot be built, loading fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+from .build import LIB, build
+
+_lib = None
+
+SR_OK, SR_E_ARG, SR_E_NOMEM, SR_E_STATE, SR_E_HIP = 0, -1, -2, -3, -4
+
+EXPORTS = ("sr_init", "sr_destroy", "sr_load_weights", "sr_prefill_chunk", "sr_decode_step", "sr_gate",
+           "sr_retire_and_compact", "sr_gate_batch", "sr_set_actions", "sr_get_actions", "sr_get_logits",
+           "sr_get_live_map", "sr_stats", "sr_strerror")
+
+
+class SrError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {strerror(status)} ({status})")
+
+
+class ModelShape(ctypes.Structure):
+    _fields_ = [("n_layers", ctypes.c_int32), ("hidden", ctypes.c_int32), ("n_q_heads", ctypes.c_int32),
+                ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("ffn", ctypes.c_int32),
+                ("vocab", ctypes.c_int32), ("rms_eps", ctypes.c_float), ("rope_theta", ctypes.c_float),
+                ("qkv_bias", ctypes.c_int32)]
+
+
+class Options(ctypes.Structure):
+    _fields_ = [("page_tokens", ctypes.c_int32), ("max_seq_len", ctypes.c_int32), ("max_turns", ctypes.c_int32),
+                ("action_mod", ctypes.c_int32), ("max_prefill_rows", ctypes.c_int32),
+                ("kv_pool_bytes", ctypes.c_uint64)]
+
+
+class LayerWeights(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in
+                ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "bq", "bk", "bv", "norm1", "norm2")]
+
+
+class Weights(ctypes.Structure):
+    _fields_ = [("embed", ctypes.c_void_p), ("lm_head", ctypes.c_void_p), ("final_norm", ctypes.c_void_p),
+                ("layers", ctypes.POINTER(LayerWeights))]
+
+
+class Stats(ctypes.Structure):
+    _fields_ = [("decoded_tokens", ctypes.c_int64), ("prefill_tokens", ctypes.c_int64)] + \
+               [(n, ctypes.c_int32) for n in ("n_live_groups", "n_live_seq", "seq_len", "turn", "pages_total",
+                                              "pages_in_use", "groups_retired", "pages_freed", "cow_page_copies")]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+def lib():
+    """Load libsr.so (building it first only if it does not exist)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB):
+            build()
+        L = ctypes.CDLL(LIB)
+        vp, ci = ctypes.c_void_p, ctypes.c_int
+        L.sr_init.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(ModelShape), ci, ci, ctypes.c_double,
+                              ctypes.POINTER(Options)]
+        L.sr_destroy.argtypes = [vp]
+        L.sr_destroy.restype = None
+        L.sr_load_weights.argtypes = [vp, ctypes.POINTER(Weights), vp]
+        L.sr_prefill_chunk.argtypes = [vp, vp, ci, ci, vp]
+        L.sr_decode_step.argtypes = [vp, vp, vp, vp]
+        L.sr_gate.argtypes = [vp, ci, vp, vp, vp]
+        L.sr_retire_and_compact.argtypes = [vp, ctypes.POINTER(ci), vp]
+        L.sr_gate_batch.argtypes = [vp, ci, ci, ci, ctypes.POINTER(ci), ci, ctypes.c_double, vp, vp, vp]
+        L.sr_set_actions.argtypes = [vp, ci, vp, vp]
+        L.sr_get_actions.argtypes = [vp, vp, vp]
+        L.sr_get_logits.argtypes = [vp, vp, vp]
+        L.sr_get_live_map.argtypes = [vp, vp]
+        L.sr_stats.argtypes = [vp, ctypes.POINTER(Stats)]
+        L.sr_strerror.argtypes = [ci]
+        L.sr_strerror.restype = ctypes.c_char_p
+        for name in EXPORTS:
+            if name not in ("sr_destroy", "sr_strerror"):
+                getattr(L, name).restype = ci
+        _lib = L
+    return _lib
+
+
+def strerror(status: int) -> str:
+    return lib().sr_strerror(status).decode()
+
+
+def _check(status: int, where: str):
+    if status != SR_OK:
+        raise SrError(status, where)
+
+
+def _ptr(t):
+    """Device (or host) address of a torch tensor / numpy array / None."""
+    if t is None:
+        return None
+    if hasattr(t, "data_ptr"):
+        return t.data_ptr()
+    return t.ctypes.data
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return getattr(stream, "cuda_stream", stream)
+
+
+def sr_gate_batch(actions, prefix_lens, threshold: float, sums=None, retire=None, stream=None):
+    """actions: device int32 [n_groups, G, stride]; sums int32 / retire uint8: device [n_lens, n_groups]."""
+    n_groups, G, stride = actions.shape
+    lens = (ctypes.c_int * len(prefix_lens))(*prefix_lens)
+    _check(lib().sr_gate_batch(_ptr(actions), n_groups, G, stride, lens, len(prefix_lens), threshold,
+                               _ptr(sums), _ptr(retire), _stream(stream)), "sr_gate_batch")
+
+
+class Context:
+    """Owns one sr_ctx.  Methods mirror the C entry points one to one."""
+
+    def __init__(self, shape, n_groups: int, G: int, threshold: float, *, page_tokens=64, max_seq_len=4096,
+                 max_turns=32, action_mod=64, max_prefill_rows=0, kv_pool_bytes=1 << 30):
+        self.shape = ModelShape(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
+                                shape.ffn, shape.vocab, shape.rms_eps, shape.rope_theta, int(shape.qkv_bias))
+        self.opt = Options(page_tokens, max_seq_len, max_turns, action_mod, max_prefill_rows, kv_pool_bytes)
+        self.G, self.n_groups0, self.vocab, self.max_turns = G, n_groups, shape.vocab, max_turns
+        self._h = ctypes.c_void_p()
+        _check(lib().sr_init(ctypes.byref(self._h), ctypes.byref(self.shape), n_groups, G, threshold,
+                             ctypes.byref(self.opt)), "sr_init")
+
+    def close(self):
+        if self._h:
+            lib().sr_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def sr_load_weights(self, embed, lm_head, final_norm, layers, stream=None):
+        """layers: list of dicts name -> device bf16 tensor (names as in sr_layer_weights)."""
+        arr = (LayerWeights * len(layers))()
+        for i, d in enumerate(layers):
+            for name, _ in LayerWeights._fields_:
+                setattr(arr[i], name, _ptr(d.get(name)))
+        w = Weights(_ptr(embed), _ptr(lm_head), _ptr(final_norm), arr)
+        _check(lib().sr_load_weights(self._h, ctypes.byref(w), _stream(stream)), "sr_load_weights")
+
+    def sr_prefill_chunk(self, tokens, shared_per_group: bool, stream=None):
+        _check(lib().sr_prefill_chunk(self._h, _ptr(tokens), tokens.shape[-1], int(shared_per_group),
+                                      _stream(stream)), "sr_prefill_chunk")
+
+    def sr_decode_step(self, forced=None, out_tokens=None, stream=None):
+        _check(lib().sr_decode_step(self._h, _ptr(forced), _ptr(out_tokens), _stream(stream)), "sr_decode_step")
+
+    def sr_gate(self, turn: int, out_sums=None, out_retire=None, stream=None):
+        _check(lib().sr_gate(self._h, turn, _ptr(out_sums), _ptr(out_retire), _stream(stream)), "sr_gate")
+
+    def sr_retire_and_compact(self, stream=None) -> int:
+        n = ctypes.c_int(-1)
+        _check(lib().sr_retire_and_compact(self._h, ctypes.byref(n), _stream(stream)), "sr_retire_and_compact")
+        return n.value
+
+    def sr_set_actions(self, turn: int, ids, stream=None):
+        _check(lib().sr_set_actions(self._h, turn, _ptr(ids), _stream(stream)), "sr_set_actions")
+
+    def sr_get_actions(self, dst, stream=None):
+        _check(lib().sr_get_actions(self._h, _ptr(dst), _stream(stream)), "sr_get_actions")
+
+    def sr_get_logits(self, dst, stream=None):
+        _check(lib().sr_get_logits(self._h, _ptr(dst), _stream(stream)), "sr_get_logits")
+
+    def sr_get_live_map(self):
+        import numpy as np
+        n = self.sr_stats()["n_live_seq"]
+        out = np.zeros(max(n, 1), dtype=np.int32)
+        _check(lib().sr_get_live_map(self._h, out.ctypes.data), "sr_get_live_map")
+        return out[:n]
+
+    def sr_stats(self) -> dict:
+        s = Stats()
+        _check(lib().sr_stats(self._h, ctypes.byref(s)), "sr_stats")
+        return s.as_dict()

@@ -1,0 +1,247 @@
+// Grouped-query attention over the paged KV cache, for decode and for chunked prefill.
+//
+// A work item is one wavefront.  It owns up to 16*RT query rows -- consecutive query tokens of
+// one unit times the n_rep query heads that share one kv head -- and one split of a token
+// range.  K and V tiles go from HBM straight into MFMA operand registers (the page layout is
+// the operand layout, so each 16-byte lane load is part of a contiguous 1 KiB run); nothing is
+// staged in LDS because a KV byte is used by exactly one wavefront.
+//
+// Per 32-token block:   S^T = K Q^T   (tokens x rows; the accumulator leaves each lane holding
+// four consecutive tokens of one query row), online softmax with the row maximum reduced by
+// two cross-lane shuffles, then  O^T += V^T P^T  where the probabilities of the two 16-token
+// tiles are packed, in-lane, into the P^T operand (the V block's slot order matches).
+// Splits leave (un-normalised O, running max, running sum); a merge kernel combines the splits
+// of the shared-prompt phase and of the private phase in fixed order.
+//
+// Group batching: during decode the prompt pages shared by the G members of a group are read
+// once per group (the members' G*n_rep query rows form the row tiles of the work item)
+// instead of once per member.
+#include "sr_internal.h"
+
+namespace sr {
+namespace {
+
+constexpr float kNegBig = -1.0e30f;
+
+template <int D, int RT>
+__global__ __launch_bounds__(256) void attn_kernel(AttnArgs a, AttnPhase p, int n_items) {
+    constexpr int KS = D / 32;     // k-steps of the QK^T contraction
+    constexpr int DT = D / 16;     // 16-wide tiles of the head dimension
+    const int lane = threadIdx.x & 63;
+    const int item = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (item >= n_items) return;
+
+    // item -> (unit, kv head, q tile, split)
+    int rest = item;
+    const int split = rest % p.n_splits; rest /= p.n_splits;
+    const int qtile = rest % p.items_per_unit; rest /= p.items_per_unit;
+    const int kvh = rest % a.n_kv;
+    const int unit = rest / a.n_kv;
+    const int n_rep = a.n_q / a.n_kv;
+
+    const int c = lane & 15, g = lane >> 4;
+
+    // query rows of this lane's column c in each row tile
+    bf16x8 qf[RT][KS];
+    int limit[RT];                  // last visible token of row (rt, c); -1 = row unused
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        const int row = rt * 16 + c;
+        const int qi = qtile * p.q_per_item + row / n_rep;       // query token within the unit
+        const int hr = row % n_rep;
+        const bool used = (row < p.q_per_item * n_rep) && (qi < p.q_per_unit);
+        limit[rt] = used ? p.causal_pos0 + qi * p.causal_stride : -1;
+        const size_t qtok = (size_t)unit * p.q_per_unit + qi;
+        const uint16_t *qp = a.q + (qtok * a.n_q + kvh * n_rep + hr) * D + 8 * g;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            uint4 raw = make_uint4(0, 0, 0, 0);
+            if (used) raw = *(const uint4 *)(qp + ks * 32);
+            qf[rt][ks] = __builtin_bit_cast(bf16x8, raw);
+        }
+    }
+
+    // token range of this split, clipped to what any row of the item can see
+    int max_limit = -1;
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) max_limit = max(max_limit, limit[rt]);
+#pragma unroll
+    for (int off = 1; off < 16; off <<= 1) max_limit = max(max_limit, __shfl_xor(max_limit, off, 64));
+    const int t_lo = p.t_begin + split * p.split_tokens;
+    const int t_hi = min(min(p.t_end, t_lo + p.split_tokens), max_limit + 1);
+
+    f32x4 o[DT][RT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) o[dt][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float mrun[RT], lrun[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) { mrun[rt] = kNegBig; lrun[rt] = 0.f; }
+
+    const int32_t *pt = a.page_table + (size_t)unit * p.pt_row_stride * a.pt_stride;
+    const int blocks_per_page = a.page_tokens >> 5;
+    const size_t block_elems = (size_t)32 * D;
+    const float scale_log2 = a.scale * 1.4426950408889634f;
+
+    for (int t0 = t_lo; t0 < t_hi; t0 += 32) {          // t_lo is a multiple of 32
+        const int page = pt[t0 / a.page_tokens];
+        const int blk = (t0 % a.page_tokens) >> 5;
+        const size_t base = (((size_t)page * a.n_kv + kvh) * blocks_per_page + blk) * block_elems;
+        const uint16_t *kb = a.kpool + base, *vb = a.vpool + base;
+
+        bf16x8 kf[2][KS];
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+                kf[tt][ks] = __builtin_bit_cast(bf16x8, *(const uint4 *)(kb + ((ks * 32 + tt * 16 + c) * 32 + 8 * g)));
+        bf16x8 vf[DT];
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+            vf[dt] = __builtin_bit_cast(bf16x8, *(const uint4 *)(vb + ((dt * 16 + c) * 32 + 8 * g)));
+
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            f32x4 s[2];
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt) {
+                s[tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks)
+                    s[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[tt][ks], qf[rt][ks], s[tt], 0, 0, 0);
+            }
+            // lane holds tokens t0 + tt*16 + 4g + e of query row (rt, c)
+            const int lim = min(limit[rt], t_hi - 1);
+            float bmax = kNegBig;
+            bool ok[2][4];
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    ok[tt][e] = (t0 + tt * 16 + 4 * g + e) <= lim;
+                    s[tt][e] = ok[tt][e] ? s[tt][e] * scale_log2 : kNegBig;
+                    bmax = fmaxf(bmax, s[tt][e]);
+                }
+            bmax = fmaxf(bmax, __shfl_xor(bmax, 16, 64));
+            bmax = fmaxf(bmax, __shfl_xor(bmax, 32, 64));
+            const float mnew = fmaxf(mrun[rt], bmax);
+            const float alpha = exp2f(mrun[rt] - mnew);
+            mrun[rt] = mnew;
+            float psum = 0.f;
+            float pv[8];
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float pe = ok[tt][e] ? exp2f(s[tt][e] - mnew) : 0.f;
+                    pv[tt * 4 + e] = pe;
+                    psum += pe;
+                }
+            lrun[rt] = lrun[rt] * alpha + psum;
+            const uint4 praw = make_uint4(pack_bf16x2(pv[0], pv[1]), pack_bf16x2(pv[2], pv[3]),
+                                          pack_bf16x2(pv[4], pv[5]), pack_bf16x2(pv[6], pv[7]));
+            const bf16x8 pf = __builtin_bit_cast(bf16x8, praw);
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                o[dt][rt] *= alpha;
+                o[dt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], pf, o[dt][rt], 0, 0, 0);
+            }
+        }
+    }
+
+    // partial results: O^T tile lane (c, g) holds head dims dt*16 + 4g..4g+3 of row (rt, c)
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        float l = lrun[rt];
+        l += __shfl_xor(l, 16, 64);
+        l += __shfl_xor(l, 32, 64);
+        const size_t prow = (size_t)item * (16 * RT) + rt * 16 + c;
+        float *po = p.part_o + prow * D;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) *(f32x4 *)(po + dt * 16 + 4 * g) = o[dt][rt];
+        if (g == 0) {
+            p.part_ml[prow * 2] = mrun[rt];
+            p.part_ml[prow * 2 + 1] = l;
+        }
+    }
+}
+
+struct MergeArgs {
+    AttnPhase ph[2];
+    int n_phases;
+    int n_q, n_kv, d, mt_total;
+    uint16_t *out;
+};
+
+// One block per (query token, query head); thread = head dimension.
+__global__ __launch_bounds__(128) void attn_merge_kernel(MergeArgs a) {
+    const int qt = blockIdx.x, h = blockIdx.y, dd = threadIdx.x;
+    if (dd >= a.d) return;
+    const int n_rep = a.n_q / a.n_kv;
+    const int kvh = h / n_rep, hr = h % n_rep;
+    float mbest = kNegBig;
+    for (int ph = 0; ph < a.n_phases; ++ph) {
+        const AttnPhase &p = a.ph[ph];
+        const int unit = qt / p.q_per_unit, qi = qt % p.q_per_unit;
+        const int qtile = qi / p.q_per_item, row = (qi % p.q_per_item) * n_rep + hr;
+        const size_t item0 = (((size_t)unit * a.n_kv + kvh) * p.items_per_unit + qtile) * p.n_splits;
+        for (int s = 0; s < p.n_splits; ++s) {
+            const size_t prow = (item0 + s) * (16 * p.rt) + row;
+            if (p.part_ml[prow * 2 + 1] > 0.f) mbest = fmaxf(mbest, p.part_ml[prow * 2]);
+        }
+    }
+    float num = 0.f, den = 0.f;
+    for (int ph = 0; ph < a.n_phases; ++ph) {
+        const AttnPhase &p = a.ph[ph];
+        const int unit = qt / p.q_per_unit, qi = qt % p.q_per_unit;
+        const int qtile = qi / p.q_per_item, row = (qi % p.q_per_item) * n_rep + hr;
+        const size_t item0 = (((size_t)unit * a.n_kv + kvh) * p.items_per_unit + qtile) * p.n_splits;
+        for (int s = 0; s < p.n_splits; ++s) {
+            const size_t prow = (item0 + s) * (16 * p.rt) + row;
+            const float l = p.part_ml[prow * 2 + 1];
+            if (l > 0.f) {
+                const float w = exp2f(p.part_ml[prow * 2] - mbest);
+                den += l * w;
+                num += p.part_o[prow * a.d + dd] * w;
+            }
+        }
+    }
+    const float r = den > 0.f ? num / den : 0.f;
+    a.out[frag_offset(qt, h * a.d + dd, a.mt_total)] = f32_to_bf16(r);
+}
+
+}  // namespace
+
+int launch_attention(const AttnArgs &a, const AttnPhase &p, hipStream_t stream) {
+    const long long n_items = (long long)p.n_units * a.n_kv * p.items_per_unit * p.n_splits;
+    if (n_items <= 0 || p.t_end <= p.t_begin) return SR_OK;
+    if (n_items > 0x7FFFFFFF || (p.t_begin & 31) || (p.split_tokens & 31) || p.split_tokens <= 0) return SR_E_ARG;
+    const int n_rep = a.n_q / a.n_kv;
+    if (p.q_per_item * n_rep > 16 * p.rt) return SR_E_ARG;
+    dim3 grid((unsigned)((n_items + 3) / 4)), block(256);
+    const int n = (int)n_items;
+    if (a.d == 128 && p.rt == 1) attn_kernel<128, 1><<<grid, block, 0, stream>>>(a, p, n);
+    else if (a.d == 128 && p.rt == 2) attn_kernel<128, 2><<<grid, block, 0, stream>>>(a, p, n);
+    else if (a.d == 64 && p.rt == 1) attn_kernel<64, 1><<<grid, block, 0, stream>>>(a, p, n);
+    else if (a.d == 64 && p.rt == 2) attn_kernel<64, 2><<<grid, block, 0, stream>>>(a, p, n);
+    else return SR_E_ARG;
+    SR_HIP(hipGetLastError());
+    return SR_OK;
+}
+
+int launch_attn_merge(const AttnArgs &a, const AttnPhase *phases, int n_phases, int n_qtok, uint4 *out,
+                      int mt_total, hipStream_t stream) {
+    if (n_qtok <= 0) return SR_OK;
+    if (n_phases < 1 || n_phases > 2) return SR_E_ARG;
+    MergeArgs m{};
+    for (int i = 0; i < n_phases; ++i) m.ph[i] = phases[i];
+    m.n_phases = n_phases;
+    m.n_q = a.n_q; m.n_kv = a.n_kv; m.d = a.d; m.mt_total = mt_total;
+    m.out = (uint16_t *)out;
+    attn_merge_kernel<<<dim3(n_qtok, a.n_q), dim3(128), 0, stream>>>(m);
+    SR_HIP(hipGetLastError());
+    return SR_OK;
+}
+
+}  // namespace sr

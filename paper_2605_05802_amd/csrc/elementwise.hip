@@ -1,0 +1,262 @@
+// Row-wise kernels between the GEMMs: residual update + RMSNorm, QKV epilogue (bias, RoPE,
+// KV page write), greedy argmax, and small utilities.  All reductions run in a fixed order
+// that does not depend on the row index or on the batch size, so a sequence's numbers do not
+// change when other rows enter or leave the batch.
+#include "sr_internal.h"
+
+namespace sr {
+namespace {
+
+// deterministic block-wide sum over 256 threads
+__device__ __forceinline__ float block_sum_256(float v, float *s_red) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) s_red[wave] = v;
+    __syncthreads();
+    const float total = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
+    __syncthreads();
+    return total;
+}
+
+// x = resid (+ partials) or embedding row; resid <- x (if write_resid); out <- bf16(x * rsqrt(mean(x^2)+eps) * gain)
+// H <= 8192: each thread keeps its (at most 4 x 8) values in registers between the two passes.
+__global__ __launch_bounds__(256) void resid_norm_kernel(NormArgs a) {
+    __shared__ float s_red[4];
+    const int m = blockIdx.x;
+    const size_t row = (size_t)(m / a.src_dup) * a.src_stride + a.src_off;
+    float *x = a.resid + row * a.H;
+    const int nvec = a.H >> 3;                       // groups of 8 consecutive features
+    float xv[4][8];
+    float ss = 0.f;
+
+    const uint16_t *e = nullptr;
+    if (a.embed) {
+        const int tok = a.tokens[(size_t)(m / a.tok_chunk) * a.tok_stride + a.tok_off + m % a.tok_chunk];
+        e = a.embed + (size_t)tok * a.H;
+    }
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int v = threadIdx.x + it * 256;
+        if (v < nvec) {
+            float *f = xv[it];
+            if (e) {
+                const uint4 raw = *(const uint4 *)(e + v * 8);
+                const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    f[2 * i] = __uint_as_float(w[i] << 16);
+                    f[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+                }
+            } else {
+                f32x4 lo = *(const f32x4 *)(x + v * 8), hi = *(const f32x4 *)(x + v * 8 + 4);
+                for (int s = 0; s < a.n_partials; ++s) {
+                    const float *p = a.partials + (size_t)s * a.partial_stride + row * a.H + v * 8;
+                    lo += *(const f32x4 *)p;
+                    hi += *(const f32x4 *)(p + 4);
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) { f[i] = lo[i]; f[4 + i] = hi[i]; }
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) ss += f[i] * f[i];
+            if (a.write_resid) {
+                *(f32x4 *)(x + v * 8) = f32x4{f[0], f[1], f[2], f[3]};
+                *(f32x4 *)(x + v * 8 + 4) = f32x4{f[4], f[5], f[6], f[7]};
+            }
+        }
+    }
+    const float total = block_sum_256(ss, s_red);
+    const float inv = 1.0f / sqrtf(total / (float)a.H + a.eps);
+
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int v = threadIdx.x + it * 256;
+        if (v < nvec) {
+            const float *f = xv[it];
+            const uint4 graw = *(const uint4 *)(a.gain + v * 8);
+            const uint32_t gw[4] = {graw.x, graw.y, graw.z, graw.w};
+            float y[8];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                y[2 * i] = f[2 * i] * inv * __uint_as_float(gw[i] << 16);
+                y[2 * i + 1] = f[2 * i + 1] * inv * __uint_as_float(gw[i] & 0xFFFF0000u);
+            }
+            uint4 o = make_uint4(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]), pack_bf16x2(y[4], y[5]),
+                                 pack_bf16x2(y[6], y[7]));
+            *(uint4 *)((uint16_t *)a.out + frag_offset(m, v * 8, a.mt_total)) = o;
+        }
+    }
+}
+
+// One 64-thread block per (row, head).  Thread i owns the rotation pair (i, i + d/2).
+__global__ __launch_bounds__(64) void qkv_post_kernel(QkvPostArgs a) {
+    const int m = blockIdx.x, head = blockIdx.y, i = threadIdx.x;
+    const int half = a.d >> 1;
+    if (i >= half) return;
+    const int unit = m / a.chunk, ci = m - unit * a.chunk;
+    const int pos = a.pos0 + ci;
+    const int q_cols = a.n_q * a.d, kv_cols = a.n_kv * a.d;
+    int col0;
+    const uint16_t *bias;
+    int kind, h;                                          // 0 q, 1 k, 2 v
+    if (head < a.n_q) { kind = 0; h = head; col0 = h * a.d; bias = a.bq ? a.bq + h * a.d : nullptr; }
+    else if (head < a.n_q + a.n_kv) { kind = 1; h = head - a.n_q; col0 = q_cols + h * a.d; bias = a.bk ? a.bk + h * a.d : nullptr; }
+    else { kind = 2; h = head - a.n_q - a.n_kv; col0 = q_cols + kv_cols + h * a.d; bias = a.bv ? a.bv + h * a.d : nullptr; }
+
+    float lo = 0.f, hi = 0.f;
+    for (int s = 0; s < a.n_partials; ++s) {
+        const float *p = a.partials + (size_t)s * a.partial_stride + (size_t)m * a.ld + col0;
+        lo += p[i];
+        hi += p[i + half];
+    }
+    if (bias) { lo += bf16_to_f32(bias[i]); hi += bf16_to_f32(bias[i + half]); }
+    if (kind != 2) {
+        const float c = a.rope_cos[(size_t)pos * half + i], s = a.rope_sin[(size_t)pos * half + i];
+        const float rlo = lo * c - hi * s, rhi = hi * c + lo * s;
+        lo = rlo; hi = rhi;
+    }
+    if (kind == 0) {
+        uint16_t *q = a.q_out + ((size_t)m * a.n_q + h) * a.d;
+        q[i] = f32_to_bf16(lo);
+        q[i + half] = f32_to_bf16(hi);
+        return;
+    }
+    const int page = a.page_table[(size_t)unit * a.pt_row_stride * a.pt_stride + pos / a.page_tokens];
+    const int tok = pos % a.page_tokens, blk = tok >> 5, t = tok & 31;
+    const size_t base = ((((size_t)page * a.n_kv + h) * (a.page_tokens >> 5)) + blk) * (size_t)(32 * a.d);
+    if (kind == 1) {
+        uint16_t *k = a.kpool + base;
+        k[(((i >> 5) * 32 + t) << 5) + (i & 31)] = f32_to_bf16(lo);
+        const int i2 = i + half;
+        k[(((i2 >> 5) * 32 + t) << 5) + (i2 & 31)] = f32_to_bf16(hi);
+    } else {
+        uint16_t *v = a.vpool + base;
+        const int slot = 8 * ((t & 15) >> 2) + 4 * (t >> 4) + (t & 3);
+        v[i * 32 + slot] = f32_to_bf16(lo);
+        v[(i + half) * 32 + slot] = f32_to_bf16(hi);
+    }
+}
+
+struct MaxIdx {
+    float v;
+    int i;
+};
+__device__ __forceinline__ MaxIdx better(MaxIdx a, MaxIdx b) {
+    return (b.v > a.v || (b.v == a.v && b.i < a.i)) ? b : a;
+}
+
+// One 1024-thread block per row: strided scan, wavefront shuffle reduction, then 16 wave results.
+__global__ __launch_bounds__(1024) void argmax_kernel(const float *__restrict__ logits, int vocab,
+                                                      const int32_t *__restrict__ forced, int32_t *greedy_out,
+                                                      int32_t *chosen, int32_t *actions, int max_turns,
+                                                      int turn_idx, int action_mod) {
+    __shared__ MaxIdx s_best[16];
+    const int r = blockIdx.x;
+    const float *row = logits + (size_t)r * vocab;
+    MaxIdx best{-INFINITY, 0x7FFFFFFF};
+    const int nvec = vocab >> 2;
+    for (int v = threadIdx.x; v < nvec; v += 1024) {
+        const f32x4 x = *(const f32x4 *)(row + v * 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) best = better(best, MaxIdx{x[e], v * 4 + e});
+    }
+    for (int v = nvec * 4 + threadIdx.x; v < vocab; v += 1024) best = better(best, MaxIdx{row[v], v});
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) {
+        MaxIdx o{__shfl_xor(best.v, off, 64), __shfl_xor(best.i, off, 64)};
+        best = better(best, o);
+    }
+    if ((threadIdx.x & 63) == 0) s_best[threadIdx.x >> 6] = best;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 16; ++w) best = better(best, s_best[w]);
+        const int greedy = best.i;
+        if (greedy_out) greedy_out[r] = greedy;
+        const int tok = forced ? forced[r] : greedy;
+        chosen[r] = tok;
+        if (actions) actions[(size_t)r * max_turns + turn_idx] = tok % action_mod;
+    }
+}
+
+__global__ void fill_i32_kernel(int32_t *dst, size_t n, int32_t value) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = value;
+}
+
+__global__ void gather_rows_kernel(uint4 *dst, const uint4 *src, const int32_t *src_rows, size_t row_vec) {
+    const int r = blockIdx.y;
+    const size_t s = (size_t)src_rows[r];
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < row_vec; i += (size_t)gridDim.x * blockDim.x)
+        dst[(size_t)r * row_vec + i] = src[s * row_vec + i];
+}
+
+__global__ void copy_page_kernel(uint4 *kpool, uint4 *vpool, size_t layer_vec, size_t page_vec, int src_page,
+                                 int dst_page) {
+    const int layer = blockIdx.y;
+    uint4 *k = kpool + layer * layer_vec, *v = vpool + layer * layer_vec;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < page_vec; i += (size_t)gridDim.x * blockDim.x) {
+        k[(size_t)dst_page * page_vec + i] = k[(size_t)src_page * page_vec + i];
+        v[(size_t)dst_page * page_vec + i] = v[(size_t)src_page * page_vec + i];
+    }
+}
+
+}  // namespace
+
+int launch_resid_norm(const NormArgs &a, hipStream_t stream) {
+    if (a.rows_out <= 0) return SR_OK;
+    if (a.H % 8 || a.H > 8192) return SR_E_ARG;
+    resid_norm_kernel<<<dim3(a.rows_out), dim3(256), 0, stream>>>(a);
+    SR_HIP(hipGetLastError());
+    return SR_OK;
+}
+
+int launch_qkv_post(const QkvPostArgs &a, hipStream_t stream) {
+    if (a.rows <= 0) return SR_OK;
+    if (a.d > 128 || a.rows > 0x7FFFFFF) return SR_E_ARG;
+    qkv_post_kernel<<<dim3(a.rows, a.n_q + 2 * a.n_kv), dim3(64), 0, stream>>>(a);
+    SR_HIP(hipGetLastError());
+    return SR_OK;
+}
+
+int launch_argmax(const float *logits, int rows, int vocab, const int32_t *forced, int32_t *greedy_out,
+                  int32_t *chosen, int32_t *actions, int max_turns, int turn_idx, int action_mod,
+                  hipStream_t stream) {
+    if (rows <= 0) return SR_OK;
+    argmax_kernel<<<dim3(rows), dim3(1024), 0, stream>>>(logits, vocab, forced, greedy_out, chosen, actions,
+                                                         max_turns, turn_idx, action_mod);
+    SR_HIP(hipGetLastError());
+    return SR_OK;
+}
+
+int launch_fill_i32(int32_t *dst, size_t n, int32_t value, hipStream_t stream) {
+    if (n == 0) return SR_OK;
+    fill_i32_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream>>>(dst, n, value);
+    SR_HIP(hipGetLastError());
+    return SR_OK;
+}
+
+int launch_gather_rows(void *dst, const void *src, const int32_t *src_rows, int n_out, size_t row_bytes,
+                       hipStream_t stream) {
+    if (n_out <= 0 || row_bytes == 0) return SR_OK;
+    if (row_bytes % 16) return SR_E_ARG;
+    const size_t row_vec = row_bytes / 16;
+    unsigned bx = (unsigned)((row_vec + 255) / 256);
+    if (bx > 256) bx = 256;
+    gather_rows_kernel<<<dim3(bx, n_out), dim3(256), 0, stream>>>((uint4 *)dst, (const uint4 *)src, src_rows, row_vec);
+    SR_HIP(hipGetLastError());
+    return SR_OK;
+}
+
+int launch_copy_page(uint16_t *kpool, uint16_t *vpool, size_t layer_stride, int n_layers, size_t page_elems,
+                     int src_page, int dst_page, hipStream_t stream) {
+    const size_t page_vec = page_elems / 8;
+    unsigned bx = (unsigned)((page_vec + 255) / 256);
+    if (bx > 64) bx = 64;
+    copy_page_kernel<<<dim3(bx, n_layers), dim3(256), 0, stream>>>((uint4 *)kpool, (uint4 *)vpool, layer_stride / 8,
+                                                                   page_vec, src_page, dst_page);
+    SR_HIP(hipGetLastError());
+    return SR_OK;
+}
+
+}  // namespace sr

@@ -1,0 +1,810 @@
+// Context, KV page bookkeeping and the C boundary (sr.h) of the selective-rollout decode library.
+//
+// The host owns the page allocator: every live sequence advances in lock step, so the pages a
+// call needs are known before anything is launched, and only the retire mask (one byte per
+// group, once per gate turn) ever flows from the device to the host.
+#include <math.h>
+#include <string.h>
+
+#include <string>
+#include <vector>
+
+#include "sr_internal.h"
+
+namespace sr {
+
+static thread_local std::string g_hip_error;
+
+void note_hip_error(hipError_t e, const char *what) {
+    g_hip_error = std::string(hipGetErrorString(e)) + " in " + what;
+}
+
+namespace {
+
+struct PackedMat {
+    uint16_t *p = nullptr;
+    int N = 0;        // valid packed rows
+    int ks = 0;       // k-steps
+};
+
+struct LayerW {
+    PackedMat qkv, o, gu, down;
+    uint16_t *bq = nullptr, *bk = nullptr, *bv = nullptr, *norm1 = nullptr, *norm2 = nullptr;
+};
+
+constexpr int kMaxSplitK = 8;
+constexpr int kMaxAttnSplits = 16;
+
+}  // namespace
+}  // namespace sr
+
+using namespace sr;
+
+struct sr_ctx {
+    sr_model_shape s{};
+    sr_options o{};
+    int n_groups0 = 0, G = 0, n_seq0 = 0;
+    double threshold = 0;
+
+    // weights (library-owned, packed)
+    bool weights_loaded = false;
+    uint16_t *embed = nullptr, *final_norm = nullptr;
+    PackedMat lm;
+    std::vector<LayerW> L;
+    float *rope_cos = nullptr, *rope_sin = nullptr;
+
+    // KV pool
+    uint16_t *kpool = nullptr, *vpool = nullptr;
+    size_t layer_stride = 0, page_elems = 0;   // elements
+    int n_pages = 0, max_pages = 0;
+    std::vector<int> refcnt, free_list;
+
+    // host batch state
+    int n_live_groups = 0, seq_len = 0, shared_tokens = 0, turn = 0, actions_recorded = 0;
+    bool first_decode_of_turn = false, have_logits = false, gate_pending = false, pt_dirty = false;
+    std::vector<int> live_orig_group;
+    std::vector<std::vector<int>> pages;       // per live sequence
+    int32_t *h_pt = nullptr;                    // pinned staging [n_seq0][max_pages]
+    uint8_t *h_retire = nullptr;                // pinned [n_groups0]
+    int32_t *h_rows = nullptr;                  // pinned [n_seq0]
+
+    // device batch state
+    int32_t *d_pt = nullptr;
+    int32_t *d_actions[2] = {nullptr, nullptr};
+    float *d_logits[2] = {nullptr, nullptr};
+    int cur = 0;
+    int32_t *d_greedy = nullptr, *d_chosen = nullptr, *d_sums = nullptr, *d_rows = nullptr;
+    uint8_t *d_retire = nullptr;
+
+    // scratch
+    int R = 0, mt_total = 0;                    // row capacity (multiple of 128) and its row tiles
+    int ks_h = 0, ks_q = 0, ks_f = 0;           // k-steps of hidden, q_dim, ffn
+    int qkv_cols = 0;
+    float *resid = nullptr, *partials = nullptr, *part_o = nullptr, *part_ml = nullptr;
+    size_t partial_elems = 0, part_rows_cap = 0;
+    uint4 *xn = nullptr, *attn_out = nullptr, *act = nullptr;
+    uint16_t *q = nullptr;
+
+    sr_stats_t st{};
+    std::vector<void *> allocs;
+
+    int n_live_seq() const { return n_live_groups * G; }
+};
+
+namespace {
+
+template <typename T>
+int dev_alloc(sr_ctx *c, T **p, size_t n_elems) {
+    void *v = nullptr;
+    hipError_t e = hipMalloc(&v, n_elems * sizeof(T) + 256);
+    if (e != hipSuccess) {
+        note_hip_error(e, "hipMalloc");
+        return e == hipErrorOutOfMemory ? SR_E_NOMEM : SR_E_HIP;
+    }
+    c->allocs.push_back(v);
+    *p = (T *)v;
+    return SR_OK;
+}
+
+int pick_splits(int M, int n_blocks, int ks_total) {
+    const int wgs = n_blocks * ceil_div(M, 128);
+    int s = ceil_div(256, wgs);
+    if (s > kMaxSplitK) s = kMaxSplitK;
+    if (s > ks_total / 8) s = ks_total / 8;
+    return s < 1 ? 1 : s;
+}
+
+int alloc_packed(sr_ctx *c, PackedMat *m, int n_rows, int K, hipStream_t st) {
+    m->N = n_rows;
+    m->ks = ceil_div(K, 32);
+    const size_t elems = (size_t)round_up(n_rows, 128) * m->ks * 32;
+    SR_TRY(dev_alloc(c, &m->p, elems));
+    SR_HIP(hipMemsetAsync(m->p, 0, elems * 2, st));
+    return SR_OK;
+}
+
+int copy_vec(sr_ctx *c, uint16_t **dst, const void *src, size_t n, hipStream_t st) {
+    SR_TRY(dev_alloc(c, dst, n));
+    SR_HIP(hipMemcpyAsync(*dst, src, n * 2, hipMemcpyDeviceToDevice, st));
+    return SR_OK;
+}
+
+int upload_page_table(sr_ctx *c, hipStream_t st) {
+    if (!c->pt_dirty) return SR_OK;
+    const int n = c->n_live_seq();
+    for (int r = 0; r < n; ++r) {
+        int32_t *row = c->h_pt + (size_t)r * c->max_pages;
+        const std::vector<int> &pg = c->pages[r];
+        for (size_t i = 0; i < pg.size(); ++i) row[i] = pg[i];
+    }
+    if (n > 0) {
+        SR_HIP(hipMemcpyAsync(c->d_pt, c->h_pt, (size_t)n * c->max_pages * 4, hipMemcpyHostToDevice, st));
+        SR_HIP(hipStreamSynchronize(st));     // the staging buffer may be rewritten by the next call
+    }
+    c->pt_dirty = false;
+    return SR_OK;
+}
+
+int take_page(sr_ctx *c) {
+    const int p = c->free_list.back();
+    c->free_list.pop_back();
+    c->st.pages_in_use++;
+    return p;
+}
+
+void drop_page(sr_ctx *c, int p, int *freed) {
+    if (--c->refcnt[p] == 0) {
+        c->free_list.push_back(p);
+        c->st.pages_in_use--;
+        ++*freed;
+    }
+}
+
+// Make room for every live sequence to grow to new_len tokens.  For a shared chunk the new
+// pages are allocated once per group and referenced by its G members.  A member about to
+// append into a page that other members still reference gets its own copy first.
+int grow_pages(sr_ctx *c, int new_len, bool shared, hipStream_t st) {
+    const int pt = c->o.page_tokens, G = c->G;
+    const int need = ceil_div(new_len, pt);
+    const int n_seq = c->n_live_seq();
+    // count first, so that a failure launches nothing and changes nothing
+    int want = 0;
+    for (int r = 0; r < n_seq; r += shared ? G : 1) {
+        const std::vector<int> &pg = c->pages[r];
+        want += need - (int)pg.size();
+        if (!shared && c->seq_len % pt != 0 && c->refcnt[pg[c->seq_len / pt]] > 1) want += 1;
+    }
+    if (want > (int)c->free_list.size()) return SR_E_NOMEM;
+
+    for (int r = 0; r < n_seq; r += shared ? G : 1) {
+        if (!shared && c->seq_len % pt != 0) {
+            const int idx = c->seq_len / pt, old = c->pages[r][idx];
+            if (c->refcnt[old] > 1) {
+                const int np = take_page(c);
+                c->refcnt[np] = 1;
+                c->refcnt[old]--;
+                c->pages[r][idx] = np;
+                SR_TRY(launch_copy_page(c->kpool, c->vpool, c->layer_stride, c->s.n_layers, c->page_elems, old, np, st));
+                c->st.cow_page_copies++;
+                c->pt_dirty = true;
+            }
+        }
+        while ((int)c->pages[r].size() < need) {
+            const int np = take_page(c);
+            if (shared) {
+                c->refcnt[np] = G;
+                for (int m = 0; m < G; ++m) c->pages[r + m].push_back(np);
+            } else {
+                c->refcnt[np] = 1;
+                c->pages[r].push_back(np);
+            }
+            c->pt_dirty = true;
+        }
+    }
+    return upload_page_table(c, st);
+}
+
+struct Pass {
+    int rows;            // rows in this pass
+    int n_units, chunk;  // rows = n_units * chunk
+    int pos0;            // absolute position of the chunk's first token
+    int pt_row0;         // page-table row of unit 0
+    int pt_row_stride;
+    const int32_t *tokens;
+    int tok_stride, tok_off;
+    bool decode;         // use the two-phase (shared prompt / private) decode attention
+    // logits
+    bool want_logits;
+    int logit_dup;       // output rows per unit (G for a shared chunk, else 1)
+    int logit_row0;      // first output row in the logits buffer
+};
+
+int gemm(sr_ctx *c, const uint4 *X, const PackedMat &W, int M, GemmEpilogue epi, void *out, int ld_out,
+         int *splits_out, hipStream_t st) {
+    GemmArgs a{};
+    a.X = X;
+    a.W = (const uint4 *)W.p;
+    a.M = M;
+    a.N = W.N;
+    a.mt_total = c->mt_total;
+    a.ks_total = W.ks;
+    a.out = out;
+    a.ld_out = ld_out;
+    a.splits = 1;
+    if (epi == EPI_F32 && splits_out) {
+        a.splits = pick_splits(M, ceil_div(W.N, 128), W.ks);
+        a.split_stride = (size_t)round_up(M, 128) * ld_out;
+        if (a.split_stride * a.splits > c->partial_elems) return SR_E_ARG;
+        *splits_out = a.splits;
+    }
+    return launch_gemm(a, epi, st);
+}
+
+int forward(sr_ctx *c, const Pass &p, hipStream_t st) {
+    const sr_model_shape &s = c->s;
+    const int M = p.rows, H = s.hidden;
+    const int n_rep = s.n_q_heads / s.n_kv_heads;
+    int n_part = 0;                  // partials of the previous projection waiting to be added to resid
+    size_t part_stride = 0;
+    const int32_t *pt = c->d_pt + (size_t)p.pt_row0 * c->max_pages;
+
+    AttnArgs aa{};
+    aa.q = c->q;
+    aa.page_table = pt;
+    aa.pt_stride = c->max_pages;
+    aa.page_tokens = c->o.page_tokens;
+    aa.n_q = s.n_q_heads;
+    aa.n_kv = s.n_kv_heads;
+    aa.d = s.head_dim;
+    aa.scale = 1.0f / sqrtf((float)s.head_dim);
+
+    // attention phases (identical for every layer)
+    AttnPhase ph[2];
+    int n_ph = 0;
+    const int ctx = p.pos0 + p.chunk;      // context length after this pass
+    size_t part_rows = 0;
+    auto add_phase = [&](AttnPhase x) {
+        const size_t items = (size_t)x.n_units * s.n_kv_heads * x.items_per_unit * x.n_splits;
+        x.part_o = c->part_o + part_rows * s.head_dim;
+        x.part_ml = c->part_ml + part_rows * 2;
+        part_rows += items * 16 * x.rt;
+        ph[n_ph++] = x;
+    };
+    if (p.decode) {
+        if (c->shared_tokens > 0) {
+            AttnPhase x{};
+            x.n_units = p.n_units / c->G;
+            x.q_per_unit = c->G;
+            x.rt = (c->G * n_rep > 16) ? 2 : 1;
+            x.q_per_item = (16 * x.rt) / n_rep < c->G ? (16 * x.rt) / n_rep : c->G;
+            x.items_per_unit = ceil_div(c->G, x.q_per_item);
+            x.pt_row_stride = c->G;
+            x.t_begin = 0;
+            x.t_end = c->shared_tokens;
+            x.causal_pos0 = ctx - 1;
+            x.causal_stride = 0;
+            x.n_splits = ceil_div(c->shared_tokens, 128);
+            if (x.n_splits > kMaxAttnSplits) x.n_splits = kMaxAttnSplits;
+            x.split_tokens = round_up(ceil_div(c->shared_tokens, x.n_splits), 32);
+            add_phase(x);
+        }
+        AttnPhase y{};
+        y.n_units = p.n_units;
+        y.q_per_unit = 1;
+        y.q_per_item = 1;
+        y.items_per_unit = 1;
+        y.rt = n_rep > 16 ? 2 : 1;
+        y.pt_row_stride = 1;
+        y.t_begin = c->shared_tokens;
+        y.t_end = ctx;
+        y.causal_pos0 = ctx - 1;
+        y.causal_stride = 0;
+        const int priv = ctx - c->shared_tokens;
+        y.n_splits = ceil_div(priv, 256);
+        if (y.n_splits > kMaxAttnSplits) y.n_splits = kMaxAttnSplits;
+        y.split_tokens = round_up(ceil_div(priv, y.n_splits), 32);
+        add_phase(y);
+    } else {
+        AttnPhase x{};
+        x.n_units = p.n_units;
+        x.q_per_unit = p.chunk;
+        x.rt = 2;
+        x.q_per_item = 32 / n_rep < p.chunk ? 32 / n_rep : p.chunk;
+        if (x.q_per_item * n_rep <= 16) x.rt = 1;
+        x.items_per_unit = ceil_div(p.chunk, x.q_per_item);
+        x.pt_row_stride = p.pt_row_stride;
+        x.t_begin = 0;
+        x.t_end = ctx;
+        x.causal_pos0 = p.pos0;
+        x.causal_stride = 1;
+        x.n_splits = 1;
+        x.split_tokens = round_up(ctx, 32);
+        add_phase(x);
+    }
+    if (part_rows > c->part_rows_cap) return SR_E_NOMEM;
+
+    for (int l = 0; l < s.n_layers; ++l) {
+        const LayerW &w = c->L[l];
+        NormArgs na{};
+        na.resid = c->resid;
+        na.out = c->xn;
+        na.rows_out = M;
+        na.src_dup = 1;
+        na.src_stride = 1;
+        na.src_off = 0;
+        na.write_resid = 1;
+        na.H = H;
+        na.mt_total = c->mt_total;
+        na.eps = s.rms_eps;
+        na.gain = w.norm1;
+        if (l == 0) {
+            na.embed = c->embed;
+            na.tokens = p.tokens;
+            na.tok_chunk = p.chunk;
+            na.tok_stride = p.tok_stride;
+            na.tok_off = p.tok_off;
+        } else {
+            na.partials = c->partials;
+            na.n_partials = n_part;
+            na.partial_stride = part_stride;
+        }
+        SR_TRY(launch_resid_norm(na, st));
+
+        int sp = 1;
+        SR_TRY(gemm(c, c->xn, w.qkv, M, EPI_F32, c->partials, c->qkv_cols, &sp, st));
+        QkvPostArgs qa{};
+        qa.partials = c->partials;
+        qa.n_partials = sp;
+        qa.partial_stride = (size_t)round_up(M, 128) * c->qkv_cols;
+        qa.ld = c->qkv_cols;
+        qa.bq = s.qkv_bias ? w.bq : nullptr;
+        qa.bk = s.qkv_bias ? w.bk : nullptr;
+        qa.bv = s.qkv_bias ? w.bv : nullptr;
+        qa.rope_cos = c->rope_cos;
+        qa.rope_sin = c->rope_sin;
+        qa.q_out = c->q;
+        qa.kpool = c->kpool + (size_t)l * c->layer_stride;
+        qa.vpool = c->vpool + (size_t)l * c->layer_stride;
+        qa.page_table = pt;
+        qa.pt_stride = c->max_pages;
+        qa.pt_row_stride = p.pt_row_stride;
+        qa.rows = M;
+        qa.chunk = p.chunk;
+        qa.pos0 = p.pos0;
+        qa.n_q = s.n_q_heads;
+        qa.n_kv = s.n_kv_heads;
+        qa.d = s.head_dim;
+        qa.page_tokens = c->o.page_tokens;
+        SR_TRY(launch_qkv_post(qa, st));
+
+        aa.kpool = qa.kpool;
+        aa.vpool = qa.vpool;
+        for (int i = 0; i < n_ph; ++i) SR_TRY(launch_attention(aa, ph[i], st));
+        SR_TRY(launch_attn_merge(aa, ph, n_ph, M, c->attn_out, c->mt_total, st));
+
+        SR_TRY(gemm(c, c->attn_out, w.o, M, EPI_F32, c->partials, H, &sp, st));
+        na.embed = nullptr;
+        na.tokens = nullptr;
+        na.partials = c->partials;
+        na.n_partials = sp;
+        na.partial_stride = (size_t)round_up(M, 128) * H;
+        na.gain = w.norm2;
+        SR_TRY(launch_resid_norm(na, st));
+
+        SR_TRY(gemm(c, c->xn, w.gu, M, EPI_SWIGLU, c->act, c->ks_f * 32, nullptr, st));
+        SR_TRY(gemm(c, c->act, w.down, M, EPI_F32, c->partials, H, &sp, st));
+        n_part = sp;
+        part_stride = (size_t)round_up(M, 128) * H;
+    }
+
+    if (p.want_logits) {
+        NormArgs na{};
+        na.resid = c->resid;
+        na.partials = c->partials;
+        na.n_partials = n_part;
+        na.partial_stride = part_stride;
+        na.gain = c->final_norm;
+        na.out = c->xn;
+        na.rows_out = p.n_units * p.logit_dup;
+        na.src_dup = p.logit_dup;
+        na.src_stride = p.chunk;
+        na.src_off = p.chunk - 1;
+        na.write_resid = 0;
+        na.H = H;
+        na.mt_total = c->mt_total;
+        na.eps = s.rms_eps;
+        SR_TRY(launch_resid_norm(na, st));
+        float *dst = c->d_logits[c->cur] + (size_t)p.logit_row0 * s.vocab;
+        SR_TRY(gemm(c, c->xn, c->lm, na.rows_out, EPI_F32, dst, s.vocab, nullptr, st));
+    }
+    return SR_OK;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------------
+// C boundary
+// ------------------------------------------------------------------------------------------------
+extern "C" {
+
+const char *sr_strerror(int status) {
+    switch (status) {
+        case SR_OK: return "ok";
+        case SR_E_ARG: return "invalid argument";
+        case SR_E_NOMEM: return "out of memory (KV page pool exhausted or allocation failed)";
+        case SR_E_STATE: return "call out of order";
+        case SR_E_HIP: return g_hip_error.empty() ? "HIP error" : g_hip_error.c_str();
+        default: return "unknown status";
+    }
+}
+
+void sr_destroy(sr_ctx *c) {
+    if (!c) return;
+    (void)hipDeviceSynchronize();
+    for (void *p : c->allocs) (void)hipFree(p);
+    if (c->h_pt) (void)hipHostFree(c->h_pt);
+    if (c->h_retire) (void)hipHostFree(c->h_retire);
+    if (c->h_rows) (void)hipHostFree(c->h_rows);
+    delete c;
+}
+
+static int init_impl(sr_ctx *c) {
+    const sr_model_shape &s = c->s;
+    const sr_options &o = c->o;
+    const int d = s.head_dim;
+    c->n_seq0 = c->n_groups0 * c->G;
+    c->qkv_cols = (s.n_q_heads + 2 * s.n_kv_heads) * d;
+    c->ks_h = s.hidden / 32;
+    c->ks_q = s.n_q_heads * d / 32;
+    c->ks_f = ceil_div(s.ffn, 32);
+    const int max_rows = o.max_prefill_rows > 0 ? o.max_prefill_rows : 8192;
+    c->R = round_up(max_rows > c->n_seq0 ? max_rows : c->n_seq0, 128);
+    c->mt_total = c->R / 16;
+
+    // RoPE tables, computed in double: angle = pos * theta^(-2i/d)
+    {
+        const int half = d / 2;
+        std::vector<float> hc((size_t)o.max_seq_len * half), hs((size_t)o.max_seq_len * half);
+        for (int i = 0; i < half; ++i) {
+            const double inv_freq = pow((double)s.rope_theta, -2.0 * i / d);
+            for (int pos = 0; pos < o.max_seq_len; ++pos) {
+                hc[(size_t)pos * half + i] = (float)cos(pos * inv_freq);
+                hs[(size_t)pos * half + i] = (float)sin(pos * inv_freq);
+            }
+        }
+        SR_TRY(dev_alloc(c, &c->rope_cos, hc.size()));
+        SR_TRY(dev_alloc(c, &c->rope_sin, hs.size()));
+        SR_HIP(hipMemcpy(c->rope_cos, hc.data(), hc.size() * 4, hipMemcpyHostToDevice));
+        SR_HIP(hipMemcpy(c->rope_sin, hs.data(), hs.size() * 4, hipMemcpyHostToDevice));
+    }
+
+    // KV pool: [layer][page][kv head][32-token block][32*d], K and V separately
+    c->page_elems = (size_t)s.n_kv_heads * o.page_tokens * d;
+    const size_t page_bytes_all = c->page_elems * 2 * s.n_layers * 2;
+    c->n_pages = (int)(o.kv_pool_bytes / page_bytes_all);
+    c->max_pages = ceil_div(o.max_seq_len, o.page_tokens);
+    if (c->n_pages < 1) return SR_E_ARG;
+    c->layer_stride = c->page_elems * c->n_pages;
+    SR_TRY(dev_alloc(c, &c->kpool, c->layer_stride * s.n_layers));
+    SR_TRY(dev_alloc(c, &c->vpool, c->layer_stride * s.n_layers));
+    // masked probabilities multiply V entries that were never written: they must be finite
+    SR_HIP(hipMemset(c->kpool, 0, c->layer_stride * s.n_layers * 2));
+    SR_HIP(hipMemset(c->vpool, 0, c->layer_stride * s.n_layers * 2));
+    c->refcnt.assign(c->n_pages, 0);
+    c->free_list.resize(c->n_pages);
+    for (int i = 0; i < c->n_pages; ++i) c->free_list[i] = c->n_pages - 1 - i;
+    c->st.pages_total = c->n_pages;
+
+    // batch state
+    c->n_live_groups = c->n_groups0;
+    c->live_orig_group.resize(c->n_groups0);
+    for (int g = 0; g < c->n_groups0; ++g) c->live_orig_group[g] = g;
+    c->pages.assign(c->n_seq0, {});
+    SR_HIP(hipHostMalloc((void **)&c->h_pt, (size_t)c->n_seq0 * c->max_pages * 4 + 16, hipHostMallocDefault));
+    SR_HIP(hipHostMalloc((void **)&c->h_retire, c->n_groups0 + 16, hipHostMallocDefault));
+    SR_HIP(hipHostMalloc((void **)&c->h_rows, (size_t)c->n_seq0 * 4 + 16, hipHostMallocDefault));
+    memset(c->h_pt, 0, (size_t)c->n_seq0 * c->max_pages * 4);
+    SR_TRY(dev_alloc(c, &c->d_pt, (size_t)c->n_seq0 * c->max_pages));
+    SR_HIP(hipMemset(c->d_pt, 0, (size_t)c->n_seq0 * c->max_pages * 4));
+    for (int i = 0; i < 2; ++i) {
+        SR_TRY(dev_alloc(c, &c->d_actions[i], (size_t)c->n_seq0 * o.max_turns));
+        SR_TRY(dev_alloc(c, &c->d_logits[i], (size_t)c->n_seq0 * s.vocab));
+        SR_TRY(launch_fill_i32(c->d_actions[i], (size_t)c->n_seq0 * o.max_turns, -1, nullptr));
+    }
+    SR_TRY(dev_alloc(c, &c->d_greedy, (size_t)c->n_seq0));
+    SR_TRY(dev_alloc(c, &c->d_chosen, (size_t)c->n_seq0));
+    SR_TRY(dev_alloc(c, &c->d_sums, (size_t)c->n_groups0));
+    SR_TRY(dev_alloc(c, &c->d_rows, (size_t)c->n_seq0));
+    SR_TRY(dev_alloc(c, &c->d_retire, (size_t)c->n_groups0));
+
+    // scratch
+    const size_t R = c->R;
+    const int n_max = c->qkv_cols > s.hidden ? c->qkv_cols : s.hidden;
+    const size_t dec_rows = round_up(c->n_seq0, 128);
+    c->partial_elems = R * n_max;
+    if (dec_rows * n_max * kMaxSplitK > c->partial_elems) c->partial_elems = dec_rows * n_max * kMaxSplitK;
+    c->part_rows_cap = 2 * R * s.n_q_heads + (size_t)c->n_seq0 * s.n_kv_heads * 32 * (2 * kMaxAttnSplits + 1);
+    SR_TRY(dev_alloc(c, &c->resid, R * s.hidden));
+    SR_TRY(dev_alloc(c, &c->partials, c->partial_elems));
+    SR_TRY(dev_alloc(c, &c->xn, R * s.hidden / 8));
+    SR_TRY(dev_alloc(c, &c->attn_out, R * (size_t)(c->ks_q * 32) / 8));
+    SR_TRY(dev_alloc(c, &c->act, R * (size_t)(c->ks_f * 32) / 8));
+    SR_TRY(dev_alloc(c, &c->q, R * (size_t)s.n_q_heads * d));
+    SR_TRY(dev_alloc(c, &c->part_o, c->part_rows_cap * d));
+    SR_TRY(dev_alloc(c, &c->part_ml, c->part_rows_cap * 2));
+    SR_HIP(hipDeviceSynchronize());
+    return SR_OK;
+}
+
+int sr_init(sr_ctx **out, const sr_model_shape *shape, int n_groups, int G, double threshold,
+            const sr_options *opt) {
+    if (!out || !shape || !opt) return SR_E_ARG;
+    *out = nullptr;
+    const sr_model_shape &s = *shape;
+    if (n_groups < 1 || G < 2 || G > 16 || !(threshold >= 0.0) || threshold > 1.0) return SR_E_ARG;
+    if (s.n_layers < 1 || s.hidden < 32 || s.hidden % 32 || s.hidden > 8192 || s.vocab < 16 || s.vocab % 16 ||
+        s.ffn < 16 || s.ffn % 16 || (s.head_dim != 64 && s.head_dim != 128) || s.n_kv_heads < 1 ||
+        s.n_q_heads % s.n_kv_heads || s.n_q_heads / s.n_kv_heads > 16 || !(s.rms_eps > 0.f) || !(s.rope_theta > 0.f))
+        return SR_E_ARG;
+    if ((opt->page_tokens != 32 && opt->page_tokens != 64 && opt->page_tokens != 128) || opt->max_seq_len < 1 ||
+        opt->max_turns < 1 || opt->max_turns > 32 || opt->action_mod < 0 || opt->max_prefill_rows < 0)
+        return SR_E_ARG;
+    sr_ctx *c = new sr_ctx();
+    c->s = s;
+    c->o = *opt;
+    c->n_groups0 = n_groups;
+    c->G = G;
+    c->threshold = threshold;
+    const int rc = init_impl(c);
+    if (rc != SR_OK) {
+        sr_destroy(c);
+        return rc;
+    }
+    *out = c;
+    return SR_OK;
+}
+
+int sr_load_weights(sr_ctx *c, const sr_weights *w, void *stream) {
+    if (!c || !w || !w->embed || !w->lm_head || !w->final_norm || !w->layers) return SR_E_ARG;
+    if (c->weights_loaded) return SR_E_STATE;
+    hipStream_t st = (hipStream_t)stream;
+    const sr_model_shape &s = c->s;
+    const int H = s.hidden, qd = s.n_q_heads * s.head_dim, kd = s.n_kv_heads * s.head_dim;
+    for (int l = 0; l < s.n_layers; ++l) {
+        const sr_layer_weights &x = w->layers[l];
+        if (!x.wq || !x.wk || !x.wv || !x.wo || !x.wg || !x.wu || !x.wd || !x.norm1 || !x.norm2) return SR_E_ARG;
+        if (s.qkv_bias && (!x.bq || !x.bk || !x.bv)) return SR_E_ARG;
+    }
+    SR_TRY(copy_vec(c, &c->embed, w->embed, (size_t)s.vocab * H, st));
+    SR_TRY(copy_vec(c, &c->final_norm, w->final_norm, H, st));
+    SR_TRY(alloc_packed(c, &c->lm, s.vocab, H, st));
+    SR_TRY(launch_pack_rows((const uint16_t *)w->lm_head, s.vocab, H, c->lm.p, c->lm.ks, 0, 0, 0, st));
+    c->L.resize(s.n_layers);
+    for (int l = 0; l < s.n_layers; ++l) {
+        const sr_layer_weights &x = w->layers[l];
+        LayerW &y = c->L[l];
+        SR_TRY(alloc_packed(c, &y.qkv, c->qkv_cols, H, st));
+        SR_TRY(launch_pack_rows((const uint16_t *)x.wq, qd, H, y.qkv.p, y.qkv.ks, 0, 0, 0, st));
+        SR_TRY(launch_pack_rows((const uint16_t *)x.wk, kd, H, y.qkv.p, y.qkv.ks, qd, 0, 0, st));
+        SR_TRY(launch_pack_rows((const uint16_t *)x.wv, kd, H, y.qkv.p, y.qkv.ks, qd + kd, 0, 0, st));
+        SR_TRY(alloc_packed(c, &y.o, H, qd, st));
+        SR_TRY(launch_pack_rows((const uint16_t *)x.wo, H, qd, y.o.p, y.o.ks, 0, 0, 0, st));
+        SR_TRY(alloc_packed(c, &y.gu, 2 * s.ffn, H, st));
+        SR_TRY(launch_pack_rows((const uint16_t *)x.wg, s.ffn, H, y.gu.p, y.gu.ks, 0, 1, 0, st));
+        SR_TRY(launch_pack_rows((const uint16_t *)x.wu, s.ffn, H, y.gu.p, y.gu.ks, 0, 1, 1, st));
+        SR_TRY(alloc_packed(c, &y.down, H, s.ffn, st));
+        SR_TRY(launch_pack_rows((const uint16_t *)x.wd, H, s.ffn, y.down.p, y.down.ks, 0, 0, 0, st));
+        if (s.qkv_bias) {
+            SR_TRY(copy_vec(c, &y.bq, x.bq, qd, st));
+            SR_TRY(copy_vec(c, &y.bk, x.bk, kd, st));
+            SR_TRY(copy_vec(c, &y.bv, x.bv, kd, st));
+        }
+        SR_TRY(copy_vec(c, &y.norm1, x.norm1, H, st));
+        SR_TRY(copy_vec(c, &y.norm2, x.norm2, H, st));
+    }
+    SR_HIP(hipStreamSynchronize(st));
+    c->weights_loaded = true;
+    return SR_OK;
+}
+
+int sr_prefill_chunk(sr_ctx *c, const int32_t *tokens, int chunk_len, int shared_per_group, void *stream) {
+    if (!c || !tokens || chunk_len <= 0) return SR_E_ARG;
+    if (!c->weights_loaded) return SR_E_STATE;
+    if (shared_per_group && c->seq_len != 0) return SR_E_STATE;
+    if (c->n_live_groups == 0) return SR_OK;
+    if (c->seq_len + chunk_len > c->o.max_seq_len) return SR_E_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    const bool shared = shared_per_group != 0;
+    const int new_len = c->seq_len + chunk_len;
+    SR_TRY(grow_pages(c, new_len, shared, st));
+
+    const int n_units = shared ? c->n_live_groups : c->n_live_seq();
+    const int dup = shared ? c->G : 1;
+    for (int c0 = 0; c0 < chunk_len; c0 += c->R) {
+        const int cl = chunk_len - c0 < c->R ? chunk_len - c0 : c->R;
+        const int upp = c->R / cl;                 // units per pass
+        for (int u0 = 0; u0 < n_units; u0 += upp) {
+            const int nu = n_units - u0 < upp ? n_units - u0 : upp;
+            Pass p{};
+            p.rows = nu * cl;
+            p.n_units = nu;
+            p.chunk = cl;
+            p.pos0 = c->seq_len + c0;
+            p.pt_row0 = u0 * dup;
+            p.pt_row_stride = dup;
+            p.tokens = tokens + (size_t)u0 * chunk_len;
+            p.tok_stride = chunk_len;
+            p.tok_off = c0;
+            p.decode = false;
+            p.want_logits = (c0 + cl == chunk_len);
+            p.logit_dup = dup;
+            p.logit_row0 = u0 * dup;
+            SR_TRY(forward(c, p, st));
+        }
+    }
+    c->seq_len = new_len;
+    if (shared) {
+        c->shared_tokens = (new_len / c->o.page_tokens) * c->o.page_tokens;
+        c->st.prefill_tokens += (int64_t)c->n_live_groups * chunk_len;
+    } else {
+        c->turn++;
+        c->first_decode_of_turn = true;
+        c->st.prefill_tokens += (int64_t)c->n_live_seq() * chunk_len;
+    }
+    c->have_logits = true;
+    return SR_OK;
+}
+
+int sr_decode_step(sr_ctx *c, const int32_t *forced, int32_t *out_tokens, void *stream) {
+    if (!c) return SR_E_ARG;
+    if (!c->weights_loaded || !c->have_logits) return SR_E_STATE;
+    if (c->n_live_groups == 0) return SR_OK;
+    if (c->seq_len + 1 > c->o.max_seq_len) return SR_E_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    const int n = c->n_live_seq();
+    SR_TRY(grow_pages(c, c->seq_len + 1, false, st));
+
+    const bool record = c->first_decode_of_turn && c->o.action_mod > 0 && c->turn >= 1 && c->turn <= c->o.max_turns;
+    SR_TRY(launch_argmax(c->d_logits[c->cur], n, c->s.vocab, forced, c->d_greedy, c->d_chosen,
+                         record ? c->d_actions[c->cur] : nullptr, c->o.max_turns, c->turn - 1,
+                         c->o.action_mod > 0 ? c->o.action_mod : 1, st));
+    if (out_tokens) SR_HIP(hipMemcpyAsync(out_tokens, c->d_greedy, (size_t)n * 4, hipMemcpyDeviceToDevice, st));
+    if (c->first_decode_of_turn && c->turn >= 1) {
+        if (record) c->actions_recorded = c->turn;
+        c->first_decode_of_turn = false;
+    }
+
+    Pass p{};
+    p.rows = n;
+    p.n_units = n;
+    p.chunk = 1;
+    p.pos0 = c->seq_len;
+    p.pt_row0 = 0;
+    p.pt_row_stride = 1;
+    p.tokens = c->d_chosen;
+    p.tok_stride = 1;
+    p.tok_off = 0;
+    p.decode = true;
+    p.want_logits = true;
+    p.logit_dup = 1;
+    p.logit_row0 = 0;
+    SR_TRY(forward(c, p, st));
+    c->seq_len += 1;
+    c->st.decoded_tokens += n;
+    return SR_OK;
+}
+
+int sr_gate(sr_ctx *c, int turn, int32_t *out_sums, uint8_t *out_retire, void *stream) {
+    if (!c || turn < 1 || turn > c->o.max_turns) return SR_E_ARG;
+    if (c->actions_recorded < turn) return SR_E_STATE;
+    hipStream_t st = (hipStream_t)stream;
+    GateLens lens{};
+    lens.n = 1;
+    lens.len[0] = turn;
+    lens.bound[0] = (int)gate_bound(c->threshold, c->G, turn);
+    const int ng = c->n_live_groups;
+    SR_TRY(launch_gate(c->d_actions[c->cur], ng, c->G, c->o.max_turns, lens, c->d_sums, c->d_retire, st));
+    if (ng > 0 && out_sums) SR_HIP(hipMemcpyAsync(out_sums, c->d_sums, (size_t)ng * 4, hipMemcpyDeviceToDevice, st));
+    if (ng > 0 && out_retire) SR_HIP(hipMemcpyAsync(out_retire, c->d_retire, (size_t)ng, hipMemcpyDeviceToDevice, st));
+    c->gate_pending = true;
+    return SR_OK;
+}
+
+int sr_retire_and_compact(sr_ctx *c, int *host_n_live_groups, void *stream) {
+    if (!c) return SR_E_ARG;
+    if (!c->gate_pending) return SR_E_STATE;
+    hipStream_t st = (hipStream_t)stream;
+    c->gate_pending = false;
+    const int ng = c->n_live_groups, G = c->G;
+    if (ng == 0) {
+        if (host_n_live_groups) *host_n_live_groups = 0;
+        return SR_OK;
+    }
+    SR_HIP(hipMemcpyAsync(c->h_retire, c->d_retire, ng, hipMemcpyDeviceToHost, st));
+    SR_HIP(hipStreamSynchronize(st));
+
+    int kept = 0, freed = 0;
+    for (int g = 0; g < ng; ++g) {
+        if (c->h_retire[g]) {
+            for (int m = 0; m < G; ++m)
+                for (int pg : c->pages[g * G + m]) drop_page(c, pg, &freed);
+            c->st.groups_retired++;
+        } else {
+            if (kept != g) {
+                c->live_orig_group[kept] = c->live_orig_group[g];
+                for (int m = 0; m < G; ++m) c->pages[kept * G + m] = std::move(c->pages[g * G + m]);
+            }
+            for (int m = 0; m < G; ++m) c->h_rows[kept * G + m] = g * G + m;
+            ++kept;
+        }
+    }
+    c->st.pages_freed += freed;
+    if (kept != ng) {
+        for (int r = kept * G; r < ng * G; ++r) c->pages[r].clear();
+        c->live_orig_group.resize(kept);
+        const int n = kept * G;
+        if (n > 0) {
+            // move the surviving rows of every per-sequence device array, keeping their order
+            SR_HIP(hipMemcpyAsync(c->d_rows, c->h_rows, (size_t)n * 4, hipMemcpyHostToDevice, st));
+            const int nxt = c->cur ^ 1;
+            SR_TRY(launch_gather_rows(c->d_actions[nxt], c->d_actions[c->cur], c->d_rows, n,
+                                      (size_t)c->o.max_turns * 4, st));
+            SR_TRY(launch_gather_rows(c->d_logits[nxt], c->d_logits[c->cur], c->d_rows, n, (size_t)c->s.vocab * 4, st));
+            c->cur = nxt;
+            SR_HIP(hipStreamSynchronize(st));     // h_rows may be rewritten by the next compaction
+        }
+        c->n_live_groups = kept;
+        c->pt_dirty = true;
+        SR_TRY(upload_page_table(c, st));
+    }
+    if (host_n_live_groups) *host_n_live_groups = kept;
+    return SR_OK;
+}
+
+int sr_set_actions(sr_ctx *c, int turn, const int32_t *ids, void *stream) {
+    if (!c || !ids || turn < 1 || turn > c->o.max_turns) return SR_E_ARG;
+    const int n = c->n_live_seq();
+    if (n == 0) return SR_OK;
+    SR_HIP(hipMemcpy2DAsync(c->d_actions[c->cur] + (turn - 1), (size_t)c->o.max_turns * 4, ids, 4, 4, n,
+                            hipMemcpyDeviceToDevice, (hipStream_t)stream));
+    if (turn > c->actions_recorded) c->actions_recorded = turn;
+    return SR_OK;
+}
+
+int sr_get_actions(sr_ctx *c, int32_t *dst, void *stream) {
+    if (!c || !dst) return SR_E_ARG;
+    const int n = c->n_live_seq();
+    if (n == 0) return SR_OK;
+    SR_HIP(hipMemcpyAsync(dst, c->d_actions[c->cur], (size_t)n * c->o.max_turns * 4, hipMemcpyDeviceToDevice,
+                          (hipStream_t)stream));
+    return SR_OK;
+}
+
+int sr_get_logits(sr_ctx *c, float *dst, void *stream) {
+    if (!c || !dst) return SR_E_ARG;
+    if (!c->have_logits) return SR_E_STATE;
+    const int n = c->n_live_seq();
+    if (n == 0) return SR_OK;
+    SR_HIP(hipMemcpyAsync(dst, c->d_logits[c->cur], (size_t)n * c->s.vocab * 4, hipMemcpyDeviceToDevice,
+                          (hipStream_t)stream));
+    return SR_OK;
+}
+
+int sr_get_live_map(sr_ctx *c, int32_t *host_orig_seq_ids) {
+    if (!c || !host_orig_seq_ids) return SR_E_ARG;
+    for (int g = 0; g < c->n_live_groups; ++g)
+        for (int m = 0; m < c->G; ++m) host_orig_seq_ids[g * c->G + m] = c->live_orig_group[g] * c->G + m;
+    return SR_OK;
+}
+
+int sr_stats(sr_ctx *c, sr_stats_t *out) {
+    if (!c || !out) return SR_E_ARG;
+    c->st.n_live_groups = c->n_live_groups;
+    c->st.n_live_seq = c->n_live_seq();
+    c->st.seq_len = c->seq_len;
+    c->st.turn = c->turn;
+    *out = c->st;
+    return SR_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,223 @@
+"""GPU rollout (prefill, decode, gate, compaction) vs the CPU checker on the same seeded inputs.
+
+Acceptance: gate sums and retired set exact; logits max-abs error <= 3e-2 (bf16 tensor-core path
+against the fp64 checker); greedy tokens identical except where the checker's top-2 gap is < 1e-2.
+The GPU is teacher-forced with the checker's tokens so that one early near-tie cannot derail
+every later comparison; its own greedy choice is still read back and compared at every step.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2605_05802_amd as sr
+import synth
+from paper_2605_05802_amd.runner import load_host_weights
+
+pytestmark = pytest.mark.gpu
+
+LOGIT_TOL = 3e-2
+GAP_RULE = 1e-2
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def run_and_compare(shape, cfg, seed, *, page_tokens=32, max_prefill_rows=0, sigma=0.02, weights=None,
+                    kv_pool_bytes=1 << 28):
+    """Runs the whole gated episode on both sides; returns (rec, stats, worst logit error, token mismatches)."""
+    w = weights if weights is not None else synth.make_weights(shape, seed=0, sigma=sigma)
+    conv = synth.converging_groups(cfg, seed)
+    prompts = synth.prompts(cfg, shape.vocab, seed)
+    obs_fn = lambda t: synth.observations(cfg, shape.vocab, seed, t, conv)
+    rec = oracle.run_episode(oracle.Model(w), prompts, obs_fn, cfg.G, cfg.turns, cfg.act_len, cfg.action_mod,
+                             cfg.gate_turns, cfg.threshold, keep_logits=True)
+
+    max_len = cfg.prompt_len + cfg.turns * (cfg.obs_len + cfg.act_len)
+    ctx = sr.Context(shape, cfg.n_groups, cfg.G, cfg.threshold, page_tokens=page_tokens, max_seq_len=max_len,
+                     max_turns=max(cfg.turns, 1), action_mod=cfg.action_mod, max_prefill_rows=max_prefill_rows,
+                     kv_pool_bytes=kv_pool_bytes)
+    load_host_weights(ctx, w)
+    ctx.sr_prefill_chunk(dev(prompts), True)
+
+    worst, mismatches, near_ties = 0.0, 0, 0
+    V = shape.vocab
+    for turn in range(cfg.turns):
+        live = rec["live_groups"][turn]
+        rows = [g * cfg.G + m for g in live for m in range(cfg.G)]
+        assert list(ctx.sr_get_live_map()) == rows
+        obs = obs_fn(turn)[rows]
+        ctx.sr_prefill_chunk(dev(obs), False)
+        logits = torch.empty((len(rows), V), dtype=torch.float32, device="cuda")
+        greedy = torch.empty(len(rows), dtype=torch.int32, device="cuda")
+        for a in range(cfg.act_len):
+            ctx.sr_get_logits(logits)
+            torch.cuda.synchronize()
+            got = logits.cpu().numpy().astype(np.float64)
+            ref = np.stack([rec["logits"][turn][a][r] for r in rows])
+            assert np.all(np.isfinite(got))
+            worst = max(worst, float(np.abs(got - ref).max()))
+            forced = rec["tokens"][turn][a, rows]
+            ctx.sr_decode_step(dev(forced), greedy)
+            torch.cuda.synchronize()
+            g = greedy.cpu().numpy()
+            gaps = rec["gaps"][turn][a, rows]
+            bad = (g != forced) & (gaps >= GAP_RULE)
+            mismatches += int(bad.sum())
+            near_ties += int(((g != forced) & (gaps < GAP_RULE)).sum())
+        K = turn + 1
+        acts = torch.empty((len(rows), max(cfg.turns, 1)), dtype=torch.int32, device="cuda")
+        ctx.sr_get_actions(acts)
+        torch.cuda.synchronize()
+        assert np.array_equal(acts.cpu().numpy()[:, :K], rec["actions"][rows, :K])
+        if K in cfg.gate_turns:
+            sums = torch.empty(len(live), dtype=torch.int32, device="cuda")
+            ret = torch.empty(len(live), dtype=torch.uint8, device="cuda")
+            ctx.sr_gate(K, sums, ret)
+            n_live = ctx.sr_retire_and_compact()
+            gate = rec["gate"][K]
+            assert list(sums.cpu().numpy()) == [gate["sums"][g] for g in live]
+            assert list(ret.cpu().numpy().astype(bool)) == [gate["cut"][g] for g in live]
+            assert n_live == sum(not gate["cut"][g] for g in live)
+    stats = ctx.sr_stats()
+    assert stats["decoded_tokens"] == rec["decoded_tokens"]
+    ctx.close()
+    return rec, stats, worst, mismatches, near_ties
+
+
+def test_tiny_config_episode():
+    """2 layers, hidden 256, 4q/2kv heads of 64, FFN 688, vocab 1024; 4 groups x 8; prompt 64;
+    6 turns of 16 observation + 8 action tokens; gate after turn 3 at 0.3."""
+    cfg = synth.TINY_EPISODE
+    rec, stats, worst, mism, near = run_and_compare(synth.TINY, cfg, seed=0)
+    print(f"tiny episode: worst |dlogit| = {worst:.3e}, token mismatches = {mism}, near ties = {near}, stats = {stats}")
+    assert worst <= LOGIT_TOL
+    assert mism == 0
+    gate = rec["gate"][3]
+    conv = synth.converging_groups(cfg, 0)
+    assert all(gate["cut"][g] for g in range(4) if conv[g])          # identical members: S = 0, retired
+    n_cut = sum(gate["cut"].values())
+    assert stats["groups_retired"] == n_cut and stats["n_live_groups"] == 4 - n_cut
+    # every page of a retired group comes back: 2 shared prompt pages + 8 members x private pages
+    priv_pages = -(-(3 * 24) // 32)
+    assert stats["pages_freed"] == n_cut * (2 + 8 * priv_pages)
+    assert stats["cow_page_copies"] == 0
+
+
+def test_larger_scale_weights_and_head_dim_128():
+    """head_dim 128, 7 query heads per kv head (the 7B grouping), larger weight scale so that attention
+    is far from uniform; sub-chunked prefill (row cap below one chunk of the whole batch)."""
+    shape = synth.ModelShape(2, 512, 14, 2, 128, 1024, 2048)
+    cfg = synth.EpisodeConfig("gqa7", 3, 8, 96, 3, 40, 4, 64, (2,), 0.3, 0.34)
+    rec, stats, worst, mism, near = run_and_compare(shape, cfg, seed=3, page_tokens=64, max_prefill_rows=256,
+                                                     sigma=0.05)
+    print(f"gqa7: worst |dlogit| = {worst:.3e}, mismatches = {mism}, near ties = {near}")
+    assert worst <= LOGIT_TOL and mism == 0
+
+
+def test_prompt_not_page_aligned_copies_on_write():
+    """Prompt of 40 tokens with 32-token pages: the second prompt page is shared until each member
+    appends to it, which must give every member a private copy without disturbing the others."""
+    shape = synth.ModelShape(1, 128, 4, 2, 64, 256, 256)
+    cfg = synth.EpisodeConfig("cow", 2, 4, 40, 2, 5, 3, 16, (), 0.3, 0.5)
+    rec, stats, worst, mism, near = run_and_compare(shape, cfg, seed=5, page_tokens=32, sigma=0.08)
+    assert stats["cow_page_copies"] == 8
+    assert worst <= LOGIT_TOL and mism == 0
+
+
+def _free_run(shape, w, cfg, seed, order, page_tokens=32):
+    """Un-forced greedy rollout with groups fed in the given order; returns logits after the last step."""
+    conv = synth.converging_groups(cfg, seed)
+    prompts = synth.prompts(cfg, shape.vocab, seed)[order]
+    max_len = cfg.prompt_len + cfg.turns * (cfg.obs_len + cfg.act_len)
+    ctx = sr.Context(shape, cfg.n_groups, cfg.G, cfg.threshold, page_tokens=page_tokens, max_seq_len=max_len,
+                     max_turns=cfg.turns, action_mod=cfg.action_mod, kv_pool_bytes=1 << 28)
+    load_host_weights(ctx, w)
+    ctx.sr_prefill_chunk(dev(prompts), True)
+    rows = np.array([g * cfg.G + m for g in order for m in range(cfg.G)])
+    toks = []
+    for turn in range(cfg.turns):
+        ctx.sr_prefill_chunk(dev(synth.observations(cfg, shape.vocab, seed, turn, conv)[rows]), False)
+        for a in range(cfg.act_len):
+            out = torch.empty(len(rows), dtype=torch.int32, device="cuda")
+            ctx.sr_decode_step(None, out)
+            toks.append(out)
+    logits = torch.empty((len(rows), shape.vocab), dtype=torch.float32, device="cuda")
+    ctx.sr_get_logits(logits)
+    torch.cuda.synchronize()
+    res = logits.cpu().numpy(), np.stack([t.cpu().numpy() for t in toks])
+    ctx.close()
+    return res
+
+
+def test_deterministic_and_permutation_invariant():
+    shape = synth.TINY
+    w = synth.make_weights(shape, seed=0)
+    cfg = synth.EpisodeConfig("perm", 4, 8, 64, 2, 16, 4, 16, (), 0.3, 0.5)
+    ident = np.arange(4)
+    l1, t1 = _free_run(shape, w, cfg, 2, ident)
+    l2, t2 = _free_run(shape, w, cfg, 2, ident)
+    assert np.array_equal(l1, l2) and np.array_equal(t1, t2)           # run twice: bit-identical
+    perm = np.array([2, 0, 3, 1])
+    l3, t3 = _free_run(shape, w, cfg, 2, perm)
+    inv_rows = np.array([g * 8 + m for g in perm for m in range(8)])
+    assert np.array_equal(l3, l1[inv_rows]) and np.array_equal(t3, t1[:, inv_rows])
+    conv = synth.converging_groups(cfg, 2)
+    for g in range(4):                                                 # identical members stay bit-identical
+        if conv[g]:
+            assert np.all(l1[g * 8:(g + 1) * 8] == l1[g * 8])
+
+
+def test_error_paths_leave_the_context_usable():
+    shape = synth.ModelShape(1, 128, 4, 2, 64, 256, 256)
+    w = synth.make_weights(shape, seed=0)
+    # pool with room for 3 pages only
+    page_bytes = 2 * 64 * 32 * 2 * 1 * 2
+    ctx = sr.Context(shape, 2, 2, 0.3, page_tokens=32, max_seq_len=256, max_turns=4, action_mod=16,
+                     kv_pool_bytes=3 * page_bytes)
+    toks = dev(np.zeros((2, 32), dtype=np.int32))
+    with pytest.raises(sr.SrError) as e:
+        ctx.sr_prefill_chunk(toks, True)
+    assert e.value.status == sr.SR_E_STATE                          # weights not loaded
+    load_host_weights(ctx, w)
+    with pytest.raises(sr.SrError) as e:
+        ctx.sr_decode_step()
+    assert e.value.status == sr.SR_E_STATE                          # decode before prefill
+    with pytest.raises(sr.SrError) as e:
+        ctx.sr_gate(1)
+    assert e.value.status == sr.SR_E_STATE                          # no action recorded yet
+    with pytest.raises(sr.SrError) as e:
+        ctx.sr_retire_and_compact()
+    assert e.value.status == sr.SR_E_STATE
+    ctx.sr_prefill_chunk(toks, True)                                 # 2 pages
+    assert ctx.sr_stats()["pages_in_use"] == 2
+    with pytest.raises(sr.SrError) as e:
+        ctx.sr_prefill_chunk(dev(np.zeros((4, 8), dtype=np.int32)), False)   # needs 4 more pages, 1 free
+    assert e.value.status == sr.SR_E_NOMEM
+    st = ctx.sr_stats()
+    assert st["pages_in_use"] == 2 and st["seq_len"] == 32           # nothing was changed
+    with pytest.raises(sr.SrError) as e:
+        ctx.sr_prefill_chunk(dev(np.zeros((4, 300), dtype=np.int32)), False)
+    assert e.value.status == sr.SR_E_ARG                            # beyond max_seq_len
+    ctx.close()
+
+
+def test_retiring_every_group_leaves_a_legal_empty_batch():
+    shape = synth.ModelShape(1, 128, 4, 2, 64, 256, 256)
+    w = synth.make_weights(shape, seed=0)
+    ctx = sr.Context(shape, 2, 4, 1.0, page_tokens=32, max_seq_len=128, max_turns=4, action_mod=16,
+                     kv_pool_bytes=1 << 24)
+    load_host_weights(ctx, w)
+    ctx.sr_prefill_chunk(dev(synth.uniform_ids(64, 0, 1, 256).reshape(2, 32)), True)
+    obs = dev(np.tile(synth.uniform_ids(8, 0, 2, 256), (8, 1)))     # same observation everywhere: S = 0
+    ctx.sr_prefill_chunk(obs, False)
+    ctx.sr_decode_step()
+    ctx.sr_gate(1)
+    assert ctx.sr_retire_and_compact() == 0
+    st = ctx.sr_stats()
+    assert st["n_live_seq"] == 0 and st["pages_in_use"] == 0 and st["groups_retired"] == 2
+    ctx.sr_prefill_chunk(obs, False)                                 # no-ops on an empty batch
+    ctx.sr_decode_step()
+    assert ctx.sr_stats()["seq_len"] == st["seq_len"]
+    ctx.close()
