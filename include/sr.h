@@ -188,6 +188,37 @@ int sr_get_live_map(sr_ctx *ctx, int32_t *host_orig_seq_ids);
 /* Counters (host struct). */
 int sr_stats(sr_ctx *ctx, sr_stats_t *host_stats);
 
+/*
+ * Per-kernel timing for benchmarks.  While enabled, every kernel launch of sr_prefill_chunk /
+ * sr_decode_step is bracketed by HIP events on the caller's stream (this perturbs the stream
+ * slightly; enable it for sampled steps only).  sr_profile_read waits for the stream, adds the
+ * elapsed times up per kernel class and clears the record.  Classes are numbered by
+ * sr_kernel_class; `out` is a HOST array of SR_KC_COUNT entries.
+ */
+typedef enum {
+    SR_KC_NORM = 0,        /* residual add + RMSNorm (+ embedding gather) */
+    SR_KC_GEMM_QKV,
+    SR_KC_QKV_POST,        /* split-K sum + bias + RoPE + KV page write */
+    SR_KC_ATTN_SHARED,     /* decode attention over the prompt pages shared by a group */
+    SR_KC_ATTN_PRIVATE,    /* decode attention over each sequence's own pages */
+    SR_KC_ATTN_PREFILL,
+    SR_KC_ATTN_MERGE,
+    SR_KC_GEMM_O,
+    SR_KC_GEMM_GATE_UP,    /* with the SwiGLU epilogue */
+    SR_KC_GEMM_DOWN,
+    SR_KC_GEMM_LM_HEAD,
+    SR_KC_ARGMAX,
+    SR_KC_COUNT
+} sr_kernel_class;
+
+typedef struct {
+    int64_t launches;
+    double total_ms;
+} sr_kernel_time;
+
+int sr_profile(sr_ctx *ctx, int enable);
+int sr_profile_read(sr_ctx *ctx, sr_kernel_time *host_out /* [SR_KC_COUNT] */, void *stream);
+
 /* Text for a status code; for SR_E_HIP the text of the last HIP error seen by this thread. */
 const char *sr_strerror(int status);
 

@@ -17,7 +17,10 @@ SR_OK, SR_E_ARG, SR_E_NOMEM, SR_E_STATE, SR_E_HIP = 0, -1, -2, -3, -4
 
 EXPORTS = ("sr_init", "sr_destroy", "sr_load_weights", "sr_prefill_chunk", "sr_decode_step", "sr_gate",
            "sr_retire_and_compact", "sr_gate_batch", "sr_set_actions", "sr_get_actions", "sr_get_logits",
-           "sr_get_live_map", "sr_stats", "sr_strerror")
+           "sr_get_live_map", "sr_stats", "sr_strerror", "sr_profile", "sr_profile_read")
+
+KERNEL_CLASSES = ("norm", "gemm_qkv", "qkv_post", "attn_shared", "attn_private", "attn_prefill", "attn_merge",
+                  "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm_head", "argmax")
 
 
 class SrError(RuntimeError):
@@ -47,6 +50,10 @@ class LayerWeights(ctypes.Structure):
 class Weights(ctypes.Structure):
     _fields_ = [("embed", ctypes.c_void_p), ("lm_head", ctypes.c_void_p), ("final_norm", ctypes.c_void_p),
                 ("layers", ctypes.POINTER(LayerWeights))]
+
+
+class KernelTime(ctypes.Structure):
+    _fields_ = [("launches", ctypes.c_int64), ("total_ms", ctypes.c_double)]
 
 
 class Stats(ctypes.Structure):
@@ -81,6 +88,8 @@ def lib():
         L.sr_get_logits.argtypes = [vp, vp, vp]
         L.sr_get_live_map.argtypes = [vp, vp]
         L.sr_stats.argtypes = [vp, ctypes.POINTER(Stats)]
+        L.sr_profile.argtypes = [vp, ci]
+        L.sr_profile_read.argtypes = [vp, ctypes.POINTER(KernelTime), vp]
         L.sr_strerror.argtypes = [ci]
         L.sr_strerror.restype = ctypes.c_char_p
         for name in EXPORTS:
@@ -186,6 +195,14 @@ class Context:
         out = np.zeros(max(n, 1), dtype=np.int32)
         _check(lib().sr_get_live_map(self._h, out.ctypes.data), "sr_get_live_map")
         return out[:n]
+
+    def sr_profile(self, enable: bool):
+        _check(lib().sr_profile(self._h, int(enable)), "sr_profile")
+
+    def sr_profile_read(self, stream=None) -> dict:
+        arr = (KernelTime * len(KERNEL_CLASSES))()
+        _check(lib().sr_profile_read(self._h, arr, _stream(stream)), "sr_profile_read")
+        return {KERNEL_CLASSES[i]: (arr[i].launches, arr[i].total_ms) for i in range(len(KERNEL_CLASSES))}
 
     def sr_stats(self) -> dict:
         s = Stats()

@@ -184,7 +184,8 @@ __global__ void fill_i32_kernel(int32_t *dst, size_t n, int32_t value) {
     if (i < n) dst[i] = value;
 }
 
-__global__ void gather_rows_kernel(uint4 *dst, const uint4 *src, const int32_t *src_rows, size_t row_vec) {
+template <typename T>
+__global__ void gather_rows_kernel(T *dst, const T *src, const int32_t *src_rows, size_t row_vec) {
     const int r = blockIdx.y;
     const size_t s = (size_t)src_rows[r];
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < row_vec; i += (size_t)gridDim.x * blockDim.x)
@@ -239,11 +240,15 @@ int launch_fill_i32(int32_t *dst, size_t n, int32_t value, hipStream_t stream) {
 int launch_gather_rows(void *dst, const void *src, const int32_t *src_rows, int n_out, size_t row_bytes,
                        hipStream_t stream) {
     if (n_out <= 0 || row_bytes == 0) return SR_OK;
-    if (row_bytes % 16) return SR_E_ARG;
-    const size_t row_vec = row_bytes / 16;
+    if (row_bytes % 4) return SR_E_ARG;
+    const bool wide = row_bytes % 16 == 0;
+    const size_t row_vec = row_bytes / (wide ? 16 : 4);
     unsigned bx = (unsigned)((row_vec + 255) / 256);
     if (bx > 256) bx = 256;
-    gather_rows_kernel<<<dim3(bx, n_out), dim3(256), 0, stream>>>((uint4 *)dst, (const uint4 *)src, src_rows, row_vec);
+    if (wide)
+        gather_rows_kernel<uint4><<<dim3(bx, n_out), dim3(256), 0, stream>>>((uint4 *)dst, (const uint4 *)src, src_rows, row_vec);
+    else
+        gather_rows_kernel<uint32_t><<<dim3(bx, n_out), dim3(256), 0, stream>>>((uint32_t *)dst, (const uint32_t *)src, src_rows, row_vec);
     SR_HIP(hipGetLastError());
     return SR_OK;
 }

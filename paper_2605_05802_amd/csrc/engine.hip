@@ -88,6 +88,12 @@ struct sr_ctx {
     sr_stats_t st{};
     std::vector<void *> allocs;
 
+    // optional per-kernel event timing
+    bool prof_on = false;
+    struct ProfRec { int kc; hipEvent_t a, b; };
+    std::vector<ProfRec> prof;
+    std::vector<hipEvent_t> event_pool;
+
     int n_live_seq() const { return n_live_groups * G; }
 };
 
@@ -104,6 +110,26 @@ int dev_alloc(sr_ctx *c, T **p, size_t n_elems) {
     c->allocs.push_back(v);
     *p = (T *)v;
     return SR_OK;
+}
+
+// Run one launch, bracketed by events when profiling is on.
+template <typename F>
+int timed(sr_ctx *c, int kc, hipStream_t st, F &&launch) {
+    if (!c->prof_on) return launch();
+    hipEvent_t ev[2];
+    for (int i = 0; i < 2; ++i) {
+        if (!c->event_pool.empty()) {
+            ev[i] = c->event_pool.back();
+            c->event_pool.pop_back();
+        } else {
+            SR_HIP(hipEventCreate(&ev[i]));
+        }
+    }
+    SR_HIP(hipEventRecord(ev[0], st));
+    const int rc = launch();
+    SR_HIP(hipEventRecord(ev[1], st));
+    c->prof.push_back({kc, ev[0], ev[1]});
+    return rc;
 }
 
 int pick_splits(int M, int n_blocks, int ks_total) {
@@ -348,10 +374,11 @@ int forward(sr_ctx *c, const Pass &p, hipStream_t st) {
             na.n_partials = n_part;
             na.partial_stride = part_stride;
         }
-        SR_TRY(launch_resid_norm(na, st));
+        SR_TRY(timed(c, SR_KC_NORM, st, [&] { return launch_resid_norm(na, st); }));
 
         int sp = 1;
-        SR_TRY(gemm(c, c->xn, w.qkv, M, EPI_F32, c->partials, c->qkv_cols, &sp, st));
+        SR_TRY(timed(c, SR_KC_GEMM_QKV, st,
+                     [&] { return gemm(c, c->xn, w.qkv, M, EPI_F32, c->partials, c->qkv_cols, &sp, st); }));
         QkvPostArgs qa{};
         qa.partials = c->partials;
         qa.n_partials = sp;
@@ -375,24 +402,32 @@ int forward(sr_ctx *c, const Pass &p, hipStream_t st) {
         qa.n_kv = s.n_kv_heads;
         qa.d = s.head_dim;
         qa.page_tokens = c->o.page_tokens;
-        SR_TRY(launch_qkv_post(qa, st));
+        SR_TRY(timed(c, SR_KC_QKV_POST, st, [&] { return launch_qkv_post(qa, st); }));
 
         aa.kpool = qa.kpool;
         aa.vpool = qa.vpool;
-        for (int i = 0; i < n_ph; ++i) SR_TRY(launch_attention(aa, ph[i], st));
-        SR_TRY(launch_attn_merge(aa, ph, n_ph, M, c->attn_out, c->mt_total, st));
+        for (int i = 0; i < n_ph; ++i) {
+            const int kc = !p.decode ? SR_KC_ATTN_PREFILL : (ph[i].q_per_unit > 1 || ph[i].pt_row_stride > 1)
+                                                              ? SR_KC_ATTN_SHARED : SR_KC_ATTN_PRIVATE;
+            SR_TRY(timed(c, kc, st, [&] { return launch_attention(aa, ph[i], st); }));
+        }
+        SR_TRY(timed(c, SR_KC_ATTN_MERGE, st,
+                     [&] { return launch_attn_merge(aa, ph, n_ph, M, c->attn_out, c->mt_total, st); }));
 
-        SR_TRY(gemm(c, c->attn_out, w.o, M, EPI_F32, c->partials, H, &sp, st));
+        SR_TRY(timed(c, SR_KC_GEMM_O, st,
+                     [&] { return gemm(c, c->attn_out, w.o, M, EPI_F32, c->partials, H, &sp, st); }));
         na.embed = nullptr;
         na.tokens = nullptr;
         na.partials = c->partials;
         na.n_partials = sp;
         na.partial_stride = (size_t)round_up(M, 128) * H;
         na.gain = w.norm2;
-        SR_TRY(launch_resid_norm(na, st));
+        SR_TRY(timed(c, SR_KC_NORM, st, [&] { return launch_resid_norm(na, st); }));
 
-        SR_TRY(gemm(c, c->xn, w.gu, M, EPI_SWIGLU, c->act, c->ks_f * 32, nullptr, st));
-        SR_TRY(gemm(c, c->act, w.down, M, EPI_F32, c->partials, H, &sp, st));
+        SR_TRY(timed(c, SR_KC_GEMM_GATE_UP, st,
+                     [&] { return gemm(c, c->xn, w.gu, M, EPI_SWIGLU, c->act, c->ks_f * 32, nullptr, st); }));
+        SR_TRY(timed(c, SR_KC_GEMM_DOWN, st,
+                     [&] { return gemm(c, c->act, w.down, M, EPI_F32, c->partials, H, &sp, st); }));
         n_part = sp;
         part_stride = (size_t)round_up(M, 128) * H;
     }
@@ -413,9 +448,10 @@ int forward(sr_ctx *c, const Pass &p, hipStream_t st) {
         na.H = H;
         na.mt_total = c->mt_total;
         na.eps = s.rms_eps;
-        SR_TRY(launch_resid_norm(na, st));
+        SR_TRY(timed(c, SR_KC_NORM, st, [&] { return launch_resid_norm(na, st); }));
         float *dst = c->d_logits[c->cur] + (size_t)p.logit_row0 * s.vocab;
-        SR_TRY(gemm(c, c->xn, c->lm, na.rows_out, EPI_F32, dst, s.vocab, nullptr, st));
+        SR_TRY(timed(c, SR_KC_GEMM_LM_HEAD, st,
+                     [&] { return gemm(c, c->xn, c->lm, na.rows_out, EPI_F32, dst, s.vocab, nullptr, st); }));
     }
     return SR_OK;
 }
@@ -445,6 +481,8 @@ void sr_destroy(sr_ctx *c) {
     if (c->h_pt) (void)hipHostFree(c->h_pt);
     if (c->h_retire) (void)hipHostFree(c->h_retire);
     if (c->h_rows) (void)hipHostFree(c->h_rows);
+    for (auto &r : c->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+    for (hipEvent_t e : c->event_pool) (void)hipEventDestroy(e);
     delete c;
 }
 
@@ -665,9 +703,11 @@ int sr_decode_step(sr_ctx *c, const int32_t *forced, int32_t *out_tokens, void *
     SR_TRY(grow_pages(c, c->seq_len + 1, false, st));
 
     const bool record = c->first_decode_of_turn && c->o.action_mod > 0 && c->turn >= 1 && c->turn <= c->o.max_turns;
-    SR_TRY(launch_argmax(c->d_logits[c->cur], n, c->s.vocab, forced, c->d_greedy, c->d_chosen,
-                         record ? c->d_actions[c->cur] : nullptr, c->o.max_turns, c->turn - 1,
-                         c->o.action_mod > 0 ? c->o.action_mod : 1, st));
+    SR_TRY(timed(c, SR_KC_ARGMAX, st, [&] {
+        return launch_argmax(c->d_logits[c->cur], n, c->s.vocab, forced, c->d_greedy, c->d_chosen,
+                             record ? c->d_actions[c->cur] : nullptr, c->o.max_turns, c->turn - 1,
+                             c->o.action_mod > 0 ? c->o.action_mod : 1, st);
+    }));
     if (out_tokens) SR_HIP(hipMemcpyAsync(out_tokens, c->d_greedy, (size_t)n * 4, hipMemcpyDeviceToDevice, st));
     if (c->first_decode_of_turn && c->turn >= 1) {
         if (record) c->actions_recorded = c->turn;
@@ -794,6 +834,28 @@ int sr_get_live_map(sr_ctx *c, int32_t *host_orig_seq_ids) {
     if (!c || !host_orig_seq_ids) return SR_E_ARG;
     for (int g = 0; g < c->n_live_groups; ++g)
         for (int m = 0; m < c->G; ++m) host_orig_seq_ids[g * c->G + m] = c->live_orig_group[g] * c->G + m;
+    return SR_OK;
+}
+
+int sr_profile(sr_ctx *c, int enable) {
+    if (!c) return SR_E_ARG;
+    c->prof_on = enable != 0;
+    return SR_OK;
+}
+
+int sr_profile_read(sr_ctx *c, sr_kernel_time *out, void *stream) {
+    if (!c || !out) return SR_E_ARG;
+    SR_HIP(hipStreamSynchronize((hipStream_t)stream));
+    for (int i = 0; i < SR_KC_COUNT; ++i) out[i] = sr_kernel_time{0, 0.0};
+    for (auto &r : c->prof) {
+        float ms = 0.f;
+        SR_HIP(hipEventElapsedTime(&ms, r.a, r.b));
+        out[r.kc].launches++;
+        out[r.kc].total_ms += ms;
+        c->event_pool.push_back(r.a);
+        c->event_pool.push_back(r.b);
+    }
+    c->prof.clear();
     return SR_OK;
 }
 

@@ -22,12 +22,14 @@ constexpr int kThreads = 256;
 constexpr int kKC = 4;                    // k-steps (of 32) per LDS chunk
 constexpr int kChunkVec = kKC * 512;      // uint4 per chunk: 8 row tiles x 64 lanes per k-step
 
-template <int EPI>
+// SKINNY = the whole batch fits one 128-row block (decode): a distinct instantiation, so that the
+// weight-streaming launches and the compute-bound prefill launches are told apart in profiles.
+template <int EPI, bool SKINNY>
 __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
     __shared__ uint4 lds[2][kChunkVec];   // 2 x 32 KiB
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-    const int nb = blockIdx.x, mb = blockIdx.y, sp = blockIdx.z;
+    const int nb = blockIdx.x, mb = SKINNY ? 0 : blockIdx.y, sp = blockIdx.z;
     const int ks_per_split = ceil_div(a.ks_total, a.splits);
     const int ks0 = sp * ks_per_split;
     const int ks1 = min(ks0 + ks_per_split, a.ks_total);
@@ -187,10 +189,14 @@ int launch_gemm(const GemmArgs &a, GemmEpilogue epi, hipStream_t stream) {
     const int m_blocks = ceil_div(a.M, 128);
     if (m_blocks * 8 > a.mt_total || a.splits < 1 || m_blocks > 65535 || a.splits > 65535) return SR_E_ARG;
     dim3 grid(n_blocks, m_blocks, epi == EPI_F32 ? a.splits : 1), block(kThreads);
-    if (epi == EPI_F32)
-        gemm_kernel<EPI_F32><<<grid, block, 0, stream>>>(a);
-    else
-        gemm_kernel<EPI_SWIGLU><<<grid, block, 0, stream>>>(a);
+    const bool skinny = m_blocks == 1;
+    if (epi == EPI_F32) {
+        if (skinny) gemm_kernel<EPI_F32, true><<<grid, block, 0, stream>>>(a);
+        else gemm_kernel<EPI_F32, false><<<grid, block, 0, stream>>>(a);
+    } else {
+        if (skinny) gemm_kernel<EPI_SWIGLU, true><<<grid, block, 0, stream>>>(a);
+        else gemm_kernel<EPI_SWIGLU, false><<<grid, block, 0, stream>>>(a);
+    }
     SR_HIP(hipGetLastError());
     return SR_OK;
 }

@@ -192,7 +192,7 @@ int launch_attn_merge(const AttnArgs &a, const AttnPhase *phases, int n_phases, 
 // misc
 // ---------------------------------------------------------------------------------------------
 int launch_fill_i32(int32_t *dst, size_t n, int32_t value, hipStream_t stream);
-// dst row r (r < n_out) = src row src_rows[r], row_bytes each (16-byte multiples)
+// dst row r (r < n_out) = src row src_rows[r], row_bytes each (multiples of 4)
 int launch_gather_rows(void *dst, const void *src, const int32_t *src_rows, int n_out, size_t row_bytes,
                        hipStream_t stream);
 // copy `tokens` leading tokens of page src to page dst for every layer and kv head

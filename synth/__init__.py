@@ -167,6 +167,69 @@ def make_weights(s: ModelShape, seed: int = 0, sigma: float = 0.02, n_layers: in
 
 
 # ----------------------------------------------------------------------------
+# device-side weight fill (same stream, same table; for multi-gigabyte models)
+# ----------------------------------------------------------------------------
+_HIP_LIB_PATH = os.path.join(_HERE, "libsrsynth_hip.so")
+_hip_lib = None
+
+
+def build_hip(force: bool = False) -> str:
+    src = os.path.join(_HERE, "srsynth_hip.hip")
+    if force or not os.path.exists(_HIP_LIB_PATH) or os.path.getmtime(_HIP_LIB_PATH) < os.path.getmtime(src):
+        subprocess.check_call(["/opt/rocm/bin/hipcc", "--offload-arch=gfx950", "-O2", "-fPIC", "-shared",
+                               "-o", _HIP_LIB_PATH, src])
+    return _HIP_LIB_PATH
+
+
+def hip_lib():
+    global _hip_lib
+    if _hip_lib is None:
+        if not os.path.exists(_HIP_LIB_PATH):
+            build_hip()
+        L = ctypes.CDLL(_HIP_LIB_PATH)
+        L.srs_fill_table16_dev.restype = ctypes.c_int
+        L.srs_fill_table16_dev.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_uint64, ctypes.c_uint64,
+                                           ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p]
+        _hip_lib = L
+    return _hip_lib
+
+
+def make_weights_device(s: ModelShape, seed: int = 0, sigma: float = 0.02, n_layers: int | None = None):
+    """The tensors of make_weights, generated directly in HBM (torch int16 tensors holding bf16 bits).
+
+    Returns (embed, lm_head, final_norm, layers) with layers a list of dicts, bit-identical to
+    make_weights(...) on the host.
+    """
+    import torch
+    L = s.n_layers if n_layers is None else n_layers
+    table = torch.from_numpy(normal_table(sigma).view(np.int16)).cuda()
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def fill(shape, stream_id):
+        t = torch.empty(shape, dtype=torch.int16, device="cuda")
+        rc = hip_lib().srs_fill_table16_dev(t.data_ptr(), t.numel(), seed, stream_id, 0, table.data_ptr(), stream)
+        if rc != 0:
+            raise RuntimeError(f"device fill failed with HIP error {rc}")
+        return t
+
+    ones = lambda n: torch.full((n,), 0x3F80, dtype=torch.int16, device="cuda")
+    embed = fill((s.vocab, s.hidden), STREAM_EMBED)
+    lm_head = fill((s.vocab, s.hidden), STREAM_LM_HEAD)
+    layers = []
+    for l in range(L):
+        d = {}
+        for name, shp in tensor_shapes(s).items():
+            if name in ("bq", "bk", "bv") and not s.qkv_bias:
+                d[name] = torch.zeros(shp, dtype=torch.int16, device="cuda")
+            else:
+                d[name] = fill(shp, layer_stream(l, name))
+        d["norm1"], d["norm2"] = ones(s.hidden), ones(s.hidden)
+        layers.append(d)
+    torch.cuda.synchronize()
+    return embed, lm_head, ones(s.hidden), layers
+
+
+# ----------------------------------------------------------------------------
 # episode inputs: shared prompts, per-turn observation chunks
 # ----------------------------------------------------------------------------
 def uniform_ids(n: int, seed: int, stream: int, modulus: int) -> np.ndarray:

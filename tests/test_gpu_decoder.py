@@ -111,7 +111,7 @@ def test_larger_scale_weights_and_head_dim_128():
     shape = synth.ModelShape(2, 512, 14, 2, 128, 1024, 2048)
     cfg = synth.EpisodeConfig("gqa7", 3, 8, 96, 3, 40, 4, 64, (2,), 0.3, 0.34)
     rec, stats, worst, mism, near = run_and_compare(shape, cfg, seed=3, page_tokens=64, max_prefill_rows=256,
-                                                     sigma=0.05)
+                                                     sigma=0.03)
     print(f"gqa7: worst |dlogit| = {worst:.3e}, mismatches = {mism}, near ties = {near}")
     assert worst <= LOGIT_TOL and mism == 0
 
@@ -122,7 +122,7 @@ def test_prompt_not_page_aligned_copies_on_write():
     shape = synth.ModelShape(1, 128, 4, 2, 64, 256, 256)
     cfg = synth.EpisodeConfig("cow", 2, 4, 40, 2, 5, 3, 16, (), 0.3, 0.5)
     rec, stats, worst, mism, near = run_and_compare(shape, cfg, seed=5, page_tokens=32, sigma=0.08)
-    assert stats["cow_page_copies"] == 8
+    assert stats["cow_page_copies"] == 2 * 3        # the last holder of a shared page keeps it
     assert worst <= LOGIT_TOL and mism == 0
 
 

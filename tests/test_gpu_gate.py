@@ -78,3 +78,15 @@ def test_gate_empty_batch_is_a_noop():
     import ctypes
     lens = (ctypes.c_int * 1)(5)
     assert sr.lib().sr_gate_batch(a.data_ptr(), 0, 8, 30, lens, 1, 0.3, None, None, None) == 0
+
+
+def test_device_weight_fill_matches_host_generator():
+    """The device fill used for multi-gigabyte models is bit-identical to the host generator."""
+    shape = synth.ModelShape(2, 128, 4, 2, 64, 256, 512)
+    host = synth.make_weights(shape, seed=7)
+    embed, lm, fn, layers = synth.make_weights_device(shape, seed=7)
+    same = lambda t, a: np.array_equal(t.cpu().numpy().view(np.uint16), a)
+    assert same(embed, host.embed) and same(lm, host.lm_head) and same(fn, host.final_norm)
+    for l in range(2):
+        for k, v in host.layers[l].items():
+            assert same(layers[l][k], v), (l, k)
