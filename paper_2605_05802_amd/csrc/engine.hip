@@ -32,7 +32,7 @@ struct LayerW {
     uint16_t *bq = nullptr, *bk = nullptr, *bv = nullptr, *norm1 = nullptr, *norm2 = nullptr;
 };
 
-constexpr int kMaxSplitK = 8;
+constexpr int kMaxSplitK = 16;
 constexpr int kMaxAttnSplits = 16;
 
 }  // namespace
@@ -132,18 +132,27 @@ int timed(sr_ctx *c, int kc, hipStream_t st, F &&launch) {
     return rc;
 }
 
-int pick_splits(int M, int n_blocks, int ks_total) {
-    const int wgs = n_blocks * ceil_div(M, 128);
-    int s = ceil_div(256, wgs);
+// Decode-time projections (M <= 128): wide matrices use the 8-wavefront kernel (256 features per
+// workgroup); thin ones are split along K so that about one workgroup per CU is in flight -- more
+// than that only adds partial-sum traffic.  Prefill (M > 128) never splits.
+bool use_wide(int M, int N, int ks_total) { return M <= 128 && (N >= 8192 || ks_total >= 256); }
+
+int pick_splits(int M, int N, int ks_total) {
+    if (M > 128) return 1;
+    const int n_blocks = ceil_div(N, use_wide(M, N, ks_total) ? 256 : 128);
+    const int target = 256 / n_blocks;
+    if (target <= 1) return 1;
+    const int units = ks_total / 8;                 // a split covers whole groups of 8 k-steps
+    const int ups = ceil_div(units, target);
+    int s = ceil_div(units, ups);
     if (s > kMaxSplitK) s = kMaxSplitK;
-    if (s > ks_total / 8) s = ks_total / 8;
     return s < 1 ? 1 : s;
 }
 
 int alloc_packed(sr_ctx *c, PackedMat *m, int n_rows, int K, hipStream_t st) {
     m->N = n_rows;
-    m->ks = ceil_div(K, 32);
-    const size_t elems = (size_t)round_up(n_rows, 128) * m->ks * 32;
+    m->ks = round_up(ceil_div(K, 32), 16);       // the GEMMs consume k-steps in groups of 16
+    const size_t elems = (size_t)round_up(n_rows, 256) * m->ks * 32;
     SR_TRY(dev_alloc(c, &m->p, elems));
     SR_HIP(hipMemsetAsync(m->p, 0, elems * 2, st));
     return SR_OK;
@@ -257,8 +266,9 @@ int gemm(sr_ctx *c, const uint4 *X, const PackedMat &W, int M, GemmEpilogue epi,
     a.out = out;
     a.ld_out = ld_out;
     a.splits = 1;
+    a.wide = use_wide(M, W.N, W.ks) ? 1 : 0;
     if (epi == EPI_F32 && splits_out) {
-        a.splits = pick_splits(M, ceil_div(W.N, 128), W.ks);
+        a.splits = pick_splits(M, W.N, W.ks);
         a.split_stride = (size_t)round_up(M, 128) * ld_out;
         if (a.split_stride * a.splits > c->partial_elems) return SR_E_ARG;
         *splits_out = a.splits;
@@ -492,9 +502,9 @@ static int init_impl(sr_ctx *c) {
     const int d = s.head_dim;
     c->n_seq0 = c->n_groups0 * c->G;
     c->qkv_cols = (s.n_q_heads + 2 * s.n_kv_heads) * d;
-    c->ks_h = s.hidden / 32;
-    c->ks_q = s.n_q_heads * d / 32;
-    c->ks_f = ceil_div(s.ffn, 32);
+    c->ks_h = round_up(s.hidden / 32, 16);       // k extents padded to groups of 16 k-steps (zeros)
+    c->ks_q = round_up(s.n_q_heads * d / 32, 16);
+    c->ks_f = round_up(ceil_div(s.ffn, 32), 16);
     const int max_rows = o.max_prefill_rows > 0 ? o.max_prefill_rows : 8192;
     c->R = round_up(max_rows > c->n_seq0 ? max_rows : c->n_seq0, 128);
     c->mt_total = c->R / 16;
@@ -564,9 +574,13 @@ static int init_impl(sr_ctx *c) {
     c->part_rows_cap = 2 * R * s.n_q_heads + (size_t)c->n_seq0 * s.n_kv_heads * 32 * (2 * kMaxAttnSplits + 1);
     SR_TRY(dev_alloc(c, &c->resid, R * s.hidden));
     SR_TRY(dev_alloc(c, &c->partials, c->partial_elems));
-    SR_TRY(dev_alloc(c, &c->xn, R * s.hidden / 8));
+    SR_TRY(dev_alloc(c, &c->xn, R * (size_t)(c->ks_h * 32) / 8));
     SR_TRY(dev_alloc(c, &c->attn_out, R * (size_t)(c->ks_q * 32) / 8));
     SR_TRY(dev_alloc(c, &c->act, R * (size_t)(c->ks_f * 32) / 8));
+    // padded k-steps are never written afterwards and must read as zero
+    SR_HIP(hipMemset(c->xn, 0, R * (size_t)(c->ks_h * 32) * 2));
+    SR_HIP(hipMemset(c->attn_out, 0, R * (size_t)(c->ks_q * 32) * 2));
+    SR_HIP(hipMemset(c->act, 0, R * (size_t)(c->ks_f * 32) * 2));
     SR_TRY(dev_alloc(c, &c->q, R * (size_t)s.n_q_heads * d));
     SR_TRY(dev_alloc(c, &c->part_o, c->part_rows_cap * d));
     SR_TRY(dev_alloc(c, &c->part_ml, c->part_rows_cap * 2));

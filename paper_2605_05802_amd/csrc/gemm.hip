@@ -18,24 +18,36 @@
 namespace sr {
 namespace {
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
 constexpr int kThreads = 256;
-constexpr int kKC = 4;                    // k-steps (of 32) per LDS chunk
+constexpr int kKC = 4;                    // k-steps (of 32) per LDS chunk of X
+constexpr int kPF = 8;                    // k-steps of W held in registers ahead of the MFMAs (two X chunks)
 constexpr int kChunkVec = kKC * 512;      // uint4 per chunk: 8 row tiles x 64 lanes per k-step
 
 // SKINNY = the whole batch fits one 128-row block (decode): a distinct instantiation, so that the
 // weight-streaming launches and the compute-bound prefill launches are told apart in profiles.
+//
+// Software pipeline per wavefront: a ring of kPF k-steps of W lives in registers; every k-step is
+// consumed by 16 MFMAs and its slot is refilled at once with the k-step kPF further on, so 16 KiB of
+// weights per wavefront are always in flight.  X chunks (kKC k-steps, 32 KiB) are double buffered
+// in LDS: the next chunk is fetched into registers while the current one is being consumed.
+// The loop body spans kPF k-steps (two X chunks) and contains no branch: the k extent of X and W is
+// padded to a multiple of kPF k-steps with zeros, every split covers whole groups of kPF k-steps,
+// prefetches past the end re-read the last valid k-step (never used), and rows of X beyond M are
+// computed and never stored.  Without branches the compiler can count outstanding loads exactly,
+// so the weight prefetch survives across the workgroup barriers.
 template <int EPI, bool SKINNY>
 __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
-    __shared__ uint4 lds[2][kChunkVec];   // 2 x 32 KiB
+    __shared__ u32x4 lds[2][kChunkVec];   // 2 x 32 KiB
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int nb = blockIdx.x, mb = SKINNY ? 0 : blockIdx.y, sp = blockIdx.z;
-    const int ks_per_split = ceil_div(a.ks_total, a.splits);
-    const int ks0 = sp * ks_per_split;
-    const int ks1 = min(ks0 + ks_per_split, a.ks_total);
+    const int units = a.ks_total / kPF;                       // groups of kPF k-steps
+    const int units_per_split = ceil_div(units, a.splits);
+    const int ks0 = sp * units_per_split * kPF;
+    const int ks1 = min(ks0 + units_per_split * kPF, a.ks_total);
     const int nt0 = nb * 8 + wave * 2;    // first of this wavefront's two 16-feature tiles
-    const int m_valid = min(128, a.M - mb * 128);
-    const int mt_valid = ceil_div(m_valid, 16);
 
     f32x4 acc[8][2];
 #pragma unroll
@@ -43,75 +55,54 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
 #pragma unroll
         for (int t = 0; t < 2; ++t) acc[i][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const uint4 *wp0 = a.W + ((size_t)nt0 * a.ks_total) * 64 + lane;
-    const uint4 *wp1 = wp0 + (size_t)a.ks_total * 64;
-    const uint4 *xp = a.X + (size_t)mb * 8 * 64;        // + (ks*mt_total)*64 + i
-
-    uint4 wcur[kKC][2], wnext[kKC][2], xnext[8];
-    const uint4 zero4 = make_uint4(0, 0, 0, 0);
-
-    auto load_w = [&](int ks, uint4 (&w)[kKC][2]) {
-#pragma unroll
-        for (int kk = 0; kk < kKC; ++kk) {
-            if (ks + kk < ks1) {
-                w[kk][0] = wp0[(size_t)(ks + kk) * 64];
-                w[kk][1] = wp1[(size_t)(ks + kk) * 64];
-            } else {
-                w[kk][0] = zero4;
-                w[kk][1] = zero4;
-            }
-        }
-    };
-    auto load_x = [&](int ks) {
-#pragma unroll
-        for (int r = 0; r < 8; ++r) {
-            const int i = tid + kThreads * r;           // uint4 index within the chunk
-            const int kk = i >> 9, within = i & 511;
-            xnext[r] = (ks + kk < ks1) ? xp[((size_t)(ks + kk) * a.mt_total) * 64 + within] : zero4;
-        }
-    };
-    auto store_x = [&](int buf) {
-#pragma unroll
-        for (int r = 0; r < 8; ++r) lds[buf][tid + kThreads * r] = xnext[r];
-    };
-
     if (ks0 < ks1) {
-        load_x(ks0);
-        load_w(ks0, wcur);
-        store_x(0);
+        const u32x4 *wp0 = (const u32x4 *)a.W + ((size_t)nt0 * a.ks_total) * 64 + lane;
+        const u32x4 *wp1 = wp0 + (size_t)a.ks_total * 64;
+        // X: thread's r-th vector of a chunk is k-step (tid + 256 r) / 512, position (tid + 256 r) % 512
+        const u32x4 *xp = (const u32x4 *)a.X + (size_t)mb * 8 * 64 + tid;
+        const size_t x_ks_stride = (size_t)a.mt_total * 64;
+        const int last = ks1 - 1;
+
+        u32x4 w0[kPF], w1[kPF], xr[8];
+#pragma unroll
+        for (int i = 0; i < kPF; ++i) {
+            w0[i] = wp0[(size_t)(ks0 + i) * 64];
+            w1[i] = wp1[(size_t)(ks0 + i) * 64];
+        }
+#pragma unroll
+        for (int r = 0; r < 8; ++r) xr[r] = xp[(size_t)(ks0 + (r >> 1)) * x_ks_stride + ((r & 1) << 8)];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) lds[0][tid + kThreads * r] = xr[r];
         __syncthreads();
-        int buf = 0;
-        for (int ks = ks0; ks < ks1; ks += kKC) {
-            const bool more = ks + kKC < ks1;
-            if (more) {
-                load_x(ks + kKC);
-                load_w(ks + kKC, wnext);
-            }
+
+        for (int ks = ks0; ks < ks1; ks += kPF) {
 #pragma unroll
-            for (int kk = 0; kk < kKC; ++kk) {
-                if (ks + kk < ks1) {
-                    const bf16x8 w0 = __builtin_bit_cast(bf16x8, wcur[kk][0]);
-                    const bf16x8 w1 = __builtin_bit_cast(bf16x8, wcur[kk][1]);
+            for (int half = 0; half < kPF / kKC; ++half) {
+                const int kc0 = ks + half * kKC;                 // first k-step of the chunk in LDS buffer `half`
 #pragma unroll
-                    for (int mt = 0; mt < 8; ++mt) {
-                        if (mt < mt_valid) {
-                            const bf16x8 x = __builtin_bit_cast(bf16x8, lds[buf][kk * 512 + mt * 64 + lane]);
-                            acc[mt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w0, x, acc[mt][0], 0, 0, 0);
-                            acc[mt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w1, x, acc[mt][1], 0, 0, 0);
-                        }
-                    }
+                for (int r = 0; r < 8; ++r) {                    // next chunk of X (clamped at the end)
+                    const int k = min(kc0 + kKC + (r >> 1), last);
+                    xr[r] = xp[(size_t)k * x_ks_stride + ((r & 1) << 8)];
                 }
-            }
-            if (more) {
-                store_x(buf ^ 1);
 #pragma unroll
                 for (int kk = 0; kk < kKC; ++kk) {
-                    wcur[kk][0] = wnext[kk][0];
-                    wcur[kk][1] = wnext[kk][1];
+                    const int i = half * kKC + kk;
+                    const bf16x8 wa = __builtin_bit_cast(bf16x8, w0[i]);
+                    const bf16x8 wb = __builtin_bit_cast(bf16x8, w1[i]);
+#pragma unroll
+                    for (int mt = 0; mt < 8; ++mt) {
+                        const bf16x8 x = __builtin_bit_cast(bf16x8, lds[half][kk * 512 + mt * 64 + lane]);
+                        acc[mt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, x, acc[mt][0], 0, 0, 0);
+                        acc[mt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wb, x, acc[mt][1], 0, 0, 0);
+                    }
+                    const int kn = min(kc0 + kk + kPF, last);    // refill the slot just consumed
+                    w0[i] = wp0[(size_t)kn * 64];
+                    w1[i] = wp1[(size_t)kn * 64];
                 }
+#pragma unroll
+                for (int r = 0; r < 8; ++r) lds[half ^ 1][tid + kThreads * r] = xr[r];
+                __syncthreads();
             }
-            __syncthreads();
-            buf ^= 1;
         }
     }
 
@@ -122,7 +113,7 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
 #pragma unroll
         for (int mt = 0; mt < 8; ++mt) {
             const int m = mb * 128 + mt * 16 + j;
-            if (mt < mt_valid && m < a.M) {
+            if (m < a.M) {
 #pragma unroll
                 for (int t = 0; t < 2; ++t) {
                     const int n = (nt0 + t) * 16 + 4 * g;
@@ -138,7 +129,140 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
 #pragma unroll
             for (int mt = 0; mt < 8; ++mt) {
                 const int m = mb * 128 + mt * 16 + j;
-                if (mt < mt_valid && m < a.M) {
+                if (m < a.M) {
+                    float r[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float gt = acc[mt][0][e];
+                        r[e] = gt / (1.0f + __expf(-gt)) * acc[mt][1][e];
+                    }
+                    uint2 v = make_uint2(pack_bf16x2(r[0], r[1]), pack_bf16x2(r[2], r[3]));
+                    *(uint2 *)(out + frag_offset(m, f, a.mt_total)) = v;
+                }
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Decode-time (M <= 128) weight-streaming kernel.
+//
+// One 8-wavefront workgroup owns 256 output features and all rows.  Vector-memory loads return in
+// order within a wavefront, so a wait for a late-issued activation load would also drain every
+// older weight load and collapse the prefetch depth.  All loads are therefore issued in order of
+// their deadline: the X chunk for two chunks ahead is fetched into registers at the start of a
+// chunk, the W k-steps for two chunks ahead are refilled during it, and the X chunk fetched during
+// the previous chunk is written to the other LDS buffer at its end.  Waiting for that write's
+// operands only forces loads that are needed immediately afterwards, so two full chunks of weights
+// (16 KiB per wavefront) stay in flight across every barrier.  No branch in the loop body: the
+// compiler counts outstanding loads exactly.
+// ---------------------------------------------------------------------------------------------
+constexpr int kSkThreads = 512;
+#ifndef SK_PF
+#define SK_PF 8
+#endif
+constexpr int kSkPF = SK_PF;            // k-steps of W in registers per wavefront (ring depth)
+constexpr int kSkBN = 256;
+constexpr int kSkXR = kChunkVec / kSkThreads;   // X vectors per thread per chunk (4)
+
+template <int EPI>
+__global__ __launch_bounds__(kSkThreads, 2) void gemm_skinny_kernel(GemmArgs a) {
+    __shared__ u32x4 lds[2][kChunkVec];   // 2 x 32 KiB
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int nb = blockIdx.x, sp = blockIdx.z;
+    const int units = a.ks_total / kSkPF;
+    const int units_per_split = ceil_div(units, a.splits);
+    const int ks0 = sp * units_per_split * kSkPF;
+    const int ks1 = min(ks0 + units_per_split * kSkPF, a.ks_total);
+    const int nt0 = nb * 16 + wave * 2;
+
+    f32x4 acc[8][2];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) acc[i][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    if (ks0 < ks1) {
+        const u32x4 *wp0 = (const u32x4 *)a.W + ((size_t)nt0 * a.ks_total) * 64 + lane;
+        const u32x4 *wp1 = wp0 + (size_t)a.ks_total * 64;
+        const int last = ks1 - 1;
+        // thread's r-th vector of a chunk: chunk index tid + 512 r -> k-step r, position tid
+        const u32x4 *xp = (const u32x4 *)a.X + tid;
+        const size_t x_ks_stride = (size_t)a.mt_total * 64;
+
+        u32x4 w0[kSkPF], w1[kSkPF], xr[2][kSkXR];
+#pragma unroll
+        for (int i = 0; i < kSkPF; ++i) {
+            w0[i] = wp0[(size_t)(ks0 + i) * 64];
+            w1[i] = wp1[(size_t)(ks0 + i) * 64];
+        }
+#pragma unroll
+        for (int r = 0; r < kSkXR; ++r) xr[0][r] = xp[(size_t)(ks0 + r) * x_ks_stride];
+#pragma unroll
+        for (int r = 0; r < kSkXR; ++r) xr[1][r] = xp[(size_t)min(ks0 + kKC + r, last) * x_ks_stride];
+#pragma unroll
+        for (int r = 0; r < kSkXR; ++r) lds[0][tid + kSkThreads * r] = xr[0][r];
+        __syncthreads();
+
+        for (int ks = ks0; ks < ks1; ks += kSkPF) {
+#pragma unroll
+            for (int q = 0; q < kSkPF / kKC; ++q) {
+                const int half = q & 1;
+                const int kc0 = ks + q * kKC;                    // chunk in LDS buffer `half`
+                __builtin_amdgcn_sched_barrier(0);               // keep the issue order = deadline order
+#pragma unroll
+                for (int r = 0; r < kSkXR; ++r)                  // X two chunks ahead
+                    xr[half][r] = xp[(size_t)min(kc0 + 2 * kKC + r, last) * x_ks_stride];
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int kk = 0; kk < kKC; ++kk) {
+                    const int i = q * kKC + kk;
+                    const bf16x8 wa = __builtin_bit_cast(bf16x8, w0[i]);
+                    const bf16x8 wb = __builtin_bit_cast(bf16x8, w1[i]);
+                    bf16x8 xf[8];
+#pragma unroll
+                    for (int mt = 0; mt < 8; ++mt)
+                        xf[mt] = __builtin_bit_cast(bf16x8, lds[half][kk * 512 + mt * 64 + lane]);
+#pragma unroll
+                    for (int mt = 0; mt < 8; ++mt) {
+                        acc[mt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, xf[mt], acc[mt][0], 0, 0, 0);
+                        acc[mt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wb, xf[mt], acc[mt][1], 0, 0, 0);
+                    }
+                    const int kn = min(kc0 + kk + kSkPF, last);    // refill the slot just consumed
+                    w0[i] = wp0[(size_t)kn * 64];
+                    w1[i] = wp1[(size_t)kn * 64];
+                }
+#pragma unroll
+                for (int r = 0; r < kSkXR; ++r)                  // X for the next chunk (fetched a chunk ago)
+                    lds[half ^ 1][tid + kSkThreads * r] = xr[half ^ 1][r];
+                __syncthreads();
+            }
+        }
+    }
+
+    const int j = lane & 15, g = lane >> 4;
+    if constexpr (EPI == EPI_F32) {
+        float *out = (float *)a.out + (size_t)sp * a.split_stride;
+#pragma unroll
+        for (int mt = 0; mt < 8; ++mt) {
+            const int m = mt * 16 + j;
+            if (m < a.M) {
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    const int n = (nt0 + t) * 16 + 4 * g;
+                    if (n < a.N) *(f32x4 *)(out + (size_t)m * a.ld_out + n) = acc[mt][t];
+                }
+            }
+        }
+    } else {
+        uint16_t *out = (uint16_t *)a.out;
+        const int f = (nt0 >> 1) * 16 + 4 * g;
+        if (f < a.ld_out) {
+#pragma unroll
+            for (int mt = 0; mt < 8; ++mt) {
+                const int m = mt * 16 + j;
+                if (m < a.M) {
                     float r[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
@@ -185,16 +309,23 @@ int launch_pack_rows(const uint16_t *src, int n_rows, int K, uint16_t *dst, int 
 
 int launch_gemm(const GemmArgs &a, GemmEpilogue epi, hipStream_t stream) {
     if (a.M <= 0) return SR_OK;
-    const int n_blocks = ceil_div(a.N, 128);
     const int m_blocks = ceil_div(a.M, 128);
-    if (m_blocks * 8 > a.mt_total || a.splits < 1 || m_blocks > 65535 || a.splits > 65535) return SR_E_ARG;
+    if (m_blocks * 8 > a.mt_total || a.splits < 1 || m_blocks > 65535 || a.splits > 65535 || a.ks_total % 16)
+        return SR_E_ARG;
+    if (m_blocks == 1 && a.wide) {
+        dim3 sgrid(ceil_div(a.N, kSkBN), 1, epi == EPI_F32 ? a.splits : 1), sblock(kSkThreads);
+        if (epi == EPI_F32) gemm_skinny_kernel<EPI_F32><<<sgrid, sblock, 0, stream>>>(a);
+        else gemm_skinny_kernel<EPI_SWIGLU><<<sgrid, sblock, 0, stream>>>(a);
+        SR_HIP(hipGetLastError());
+        return SR_OK;
+    }
+    const int n_blocks = ceil_div(a.N, 128);
     dim3 grid(n_blocks, m_blocks, epi == EPI_F32 ? a.splits : 1), block(kThreads);
-    const bool skinny = m_blocks == 1;
-    if (epi == EPI_F32) {
-        if (skinny) gemm_kernel<EPI_F32, true><<<grid, block, 0, stream>>>(a);
-        else gemm_kernel<EPI_F32, false><<<grid, block, 0, stream>>>(a);
+    if (m_blocks == 1) {
+        if (epi == EPI_F32) gemm_kernel<EPI_F32, true><<<grid, block, 0, stream>>>(a);
+        else gemm_kernel<EPI_SWIGLU, true><<<grid, block, 0, stream>>>(a);
     } else {
-        if (skinny) gemm_kernel<EPI_SWIGLU, true><<<grid, block, 0, stream>>>(a);
+        if (epi == EPI_F32) gemm_kernel<EPI_F32, false><<<grid, block, 0, stream>>>(a);
         else gemm_kernel<EPI_SWIGLU, false><<<grid, block, 0, stream>>>(a);
     }
     SR_HIP(hipGetLastError());
