@@ -141,6 +141,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="7b-g8-16groups", choices=["7b-g8-16groups", "tiny"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layers", type=int, default=0,
+                    help="counter collection only: truncate the model to this many layers (not a valid headline run)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference for scaling HBM traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (groups are independent; see DESIGN.md for how the "
@@ -160,8 +164,20 @@ def main():
     else:
         shape, cfg = synth.QWEN7B, synth.C3_EPISODE
     turns = min(args.steps, cfg.turns)
+    if args.layers > 0:
+        import dataclasses
+        shape = dataclasses.replace(shape, n_layers=args.layers)
+        cfg = dataclasses.replace(cfg, prompt_len=64)
 
+    if args.calibrate_copy:
+        src = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)                      # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
+    print("bench: generating weights", file=sys.stderr, flush=True)
     weights = synth.make_weights_device(shape, seed=0)
+    print("bench: running", file=sys.stderr, flush=True)
     if args.warmup > 0:
         run_episode(sr, torch, synth, shape, cfg, weights, min(args.warmup, cfg.turns), 0, None)
     res = run_episode(sr, torch, synth, shape, cfg, weights, turns, 0, profile_step=cfg.act_len // 2)
