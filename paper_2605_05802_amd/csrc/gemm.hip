@@ -84,21 +84,43 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
                     const int k = min(kc0 + kKC + (r >> 1), last);
                     xr[r] = xp[(size_t)k * x_ks_stride + ((r & 1) << 8)];
                 }
+                __builtin_amdgcn_sched_barrier(0);
+                // X fragments come from LDS one k-step ahead of their MFMAs, the two streams interleaved
+                bf16x8 xf[2][8];
+#pragma unroll
+                for (int mt = 0; mt < 8; ++mt)
+                    xf[0][mt] = __builtin_bit_cast(bf16x8, lds[half][mt * 64 + lane]);
 #pragma unroll
                 for (int kk = 0; kk < kKC; ++kk) {
                     const int i = half * kKC + kk;
+                    __builtin_amdgcn_sched_barrier(0);
                     const bf16x8 wa = __builtin_bit_cast(bf16x8, w0[i]);
                     const bf16x8 wb = __builtin_bit_cast(bf16x8, w1[i]);
+                    if (kk + 1 < kKC) {
+#pragma unroll
+                        for (int mt = 0; mt < 8; ++mt)
+                            xf[(kk + 1) & 1][mt] = __builtin_bit_cast(bf16x8, lds[half][(kk + 1) * 512 + mt * 64 + lane]);
+                    }
 #pragma unroll
                     for (int mt = 0; mt < 8; ++mt) {
-                        const bf16x8 x = __builtin_bit_cast(bf16x8, lds[half][kk * 512 + mt * 64 + lane]);
-                        acc[mt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, x, acc[mt][0], 0, 0, 0);
-                        acc[mt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wb, x, acc[mt][1], 0, 0, 0);
+                        acc[mt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, xf[kk & 1][mt], acc[mt][0], 0, 0, 0);
+                        acc[mt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wb, xf[kk & 1][mt], acc[mt][1], 0, 0, 0);
                     }
                     const int kn = min(kc0 + kk + kPF, last);    // refill the slot just consumed
                     w0[i] = wp0[(size_t)kn * 64];
                     w1[i] = wp1[(size_t)kn * 64];
+                    if (kk + 1 < kKC) {
+#pragma unroll
+                        for (int mt = 0; mt < 8; ++mt) {
+                            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);   // 2 MFMA
+                            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 LDS read
+                        }
+                    } else {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
+                    }
+                    __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);           // W refills
                 }
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int r = 0; r < 8; ++r) lds[half ^ 1][tid + kThreads * r] = xr[r];
                 __syncthreads();
@@ -165,6 +187,11 @@ constexpr int kSkPF = SK_PF;            // k-steps of W in registers per wavefro
 constexpr int kSkBN = 256;
 constexpr int kSkXR = kChunkVec / kSkThreads;   // X vectors per thread per chunk (4)
 
+// The MFMA used here is the 32x32x16 form: with one workgroup per CU all eight wavefronts stall at
+// the same barriers, and a single wavefront keeps the matrix pipe far busier with 32x32 tiles than
+// with 16x16 ones.  Its operands (32 rows x 16 k) are assembled from the same 16-row fragment layout
+// by addressing: lane (r = lane % 32, g = lane / 32) of k-half h takes the 16 bytes of row tile r / 16,
+// lane slot (r % 16) + 16 * (2h + g).
 template <int EPI>
 __global__ __launch_bounds__(kSkThreads, 2) void gemm_skinny_kernel(GemmArgs a) {
     __shared__ u32x4 lds[2][kChunkVec];   // 2 x 32 KiB
@@ -175,21 +202,25 @@ __global__ __launch_bounds__(kSkThreads, 2) void gemm_skinny_kernel(GemmArgs a) 
     const int units_per_split = ceil_div(units, a.splits);
     const int ks0 = sp * units_per_split * kSkPF;
     const int ks1 = min(ks0 + units_per_split * kSkPF, a.ks_total);
-    const int nt0 = nb * 16 + wave * 2;
+    const int nt32 = nb * 8 + wave;                 // this wavefront's 32 output features
+    const int r32 = lane & 31, g2 = lane >> 5;
+    const int sub = r32 >> 4;                       // which 16-row tile of the pair
+    const int slot0 = (r32 & 15) + 16 * g2;         // lane slot for k-half 0; k-half 1 is +32
 
-    f32x4 acc[8][2];
+    f32x16 acc[4];
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int t = 0; t < 2; ++t) acc[i][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
 
     if (ks0 < ks1) {
-        const u32x4 *wp0 = (const u32x4 *)a.W + ((size_t)nt0 * a.ks_total) * 64 + lane;
-        const u32x4 *wp1 = wp0 + (size_t)a.ks_total * 64;
+        const u32x4 *wp0 = (const u32x4 *)a.W + ((size_t)(nt32 * 2 + sub) * a.ks_total) * 64 + slot0;
+        const u32x4 *wp1 = wp0 + 32;
         const int last = ks1 - 1;
         // thread's r-th vector of a chunk: chunk index tid + 512 r -> k-step r, position tid
         const u32x4 *xp = (const u32x4 *)a.X + tid;
         const size_t x_ks_stride = (size_t)a.mt_total * 64;
+        const int xoff = sub * 64 + slot0;          // + mt32 * 128 + h * 32 inside a k-step of a buffer
 
         u32x4 w0[kSkPF], w1[kSkPF], xr[2][kSkXR];
 #pragma unroll
@@ -215,24 +246,45 @@ __global__ __launch_bounds__(kSkThreads, 2) void gemm_skinny_kernel(GemmArgs a) 
                 for (int r = 0; r < kSkXR; ++r)                  // X two chunks ahead
                     xr[half][r] = xp[(size_t)min(kc0 + 2 * kKC + r, last) * x_ks_stride];
                 __builtin_amdgcn_sched_barrier(0);
+                // X fragments are fetched from LDS one k-step ahead of the MFMAs that use them and the
+                // two instruction streams are interleaved explicitly.
+                bf16x8 xf[2][8];                                 // [parity][mt32 * 2 + k-half]
+                const u32x4 *xb = &lds[half][xoff];
+#pragma unroll
+                for (int f = 0; f < 8; ++f)
+                    xf[0][f] = __builtin_bit_cast(bf16x8, xb[(f >> 1) * 128 + (f & 1) * 32]);
 #pragma unroll
                 for (int kk = 0; kk < kKC; ++kk) {
                     const int i = q * kKC + kk;
+                    __builtin_amdgcn_sched_barrier(0);
                     const bf16x8 wa = __builtin_bit_cast(bf16x8, w0[i]);
                     const bf16x8 wb = __builtin_bit_cast(bf16x8, w1[i]);
-                    bf16x8 xf[8];
+                    if (kk + 1 < kKC) {
 #pragma unroll
-                    for (int mt = 0; mt < 8; ++mt)
-                        xf[mt] = __builtin_bit_cast(bf16x8, lds[half][kk * 512 + mt * 64 + lane]);
-#pragma unroll
-                    for (int mt = 0; mt < 8; ++mt) {
-                        acc[mt][0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa, xf[mt], acc[mt][0], 0, 0, 0);
-                        acc[mt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wb, xf[mt], acc[mt][1], 0, 0, 0);
+                        for (int f = 0; f < 8; ++f)
+                            xf[(kk + 1) & 1][f] =
+                                __builtin_bit_cast(bf16x8, xb[(kk + 1) * 512 + (f >> 1) * 128 + (f & 1) * 32]);
                     }
-                    const int kn = min(kc0 + kk + kSkPF, last);    // refill the slot just consumed
+#pragma unroll
+                    for (int mt = 0; mt < 4; ++mt) {
+                        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa, xf[kk & 1][mt * 2], acc[mt], 0, 0, 0);
+                        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb, xf[kk & 1][mt * 2 + 1], acc[mt], 0, 0, 0);
+                    }
+                    const int kn = min(kc0 + kk + kSkPF, last);  // refill the slot just consumed
                     w0[i] = wp0[(size_t)kn * 64];
                     w1[i] = wp1[(size_t)kn * 64];
+                    if (kk + 1 < kKC) {
+#pragma unroll
+                        for (int f = 0; f < 8; ++f) {
+                            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
+                            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 LDS read
+                        }
+                    } else {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+                    }
+                    __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);           // W refills
                 }
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int r = 0; r < kSkXR; ++r)                  // X for the next chunk (fetched a chunk ago)
                     lds[half ^ 1][tid + kSkThreads * r] = xr[half ^ 1][r];
@@ -241,36 +293,43 @@ __global__ __launch_bounds__(kSkThreads, 2) void gemm_skinny_kernel(GemmArgs a) 
         }
     }
 
-    const int j = lane & 15, g = lane >> 4;
+    // accumulator of row tile mt: lane (r32 = batch row within the tile, g2) holds, in register v,
+    // output feature 8 * (v / 4) + 4 * g2 + v % 4 of the wavefront's 32
     if constexpr (EPI == EPI_F32) {
         float *out = (float *)a.out + (size_t)sp * a.split_stride;
 #pragma unroll
-        for (int mt = 0; mt < 8; ++mt) {
-            const int m = mt * 16 + j;
+        for (int mt = 0; mt < 4; ++mt) {
+            const int m = mt * 32 + r32;
             if (m < a.M) {
 #pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    const int n = (nt0 + t) * 16 + 4 * g;
-                    if (n < a.N) *(f32x4 *)(out + (size_t)m * a.ld_out + n) = acc[mt][t];
+                for (int vq = 0; vq < 4; ++vq) {
+                    const int n = nt32 * 32 + 8 * vq + 4 * g2;
+                    if (n < a.N)
+                        *(f32x4 *)(out + (size_t)m * a.ld_out + n) =
+                            f32x4{acc[mt][4 * vq], acc[mt][4 * vq + 1], acc[mt][4 * vq + 2], acc[mt][4 * vq + 3]};
                 }
             }
         }
     } else {
+        // packed rows 0..15 of the 32 are gate features, 16..31 the matching up features
         uint16_t *out = (uint16_t *)a.out;
-        const int f = (nt0 >> 1) * 16 + 4 * g;
-        if (f < a.ld_out) {
 #pragma unroll
-            for (int mt = 0; mt < 8; ++mt) {
-                const int m = mt * 16 + j;
-                if (m < a.M) {
-                    float r[4];
+        for (int mt = 0; mt < 4; ++mt) {
+            const int m = mt * 32 + r32;
+            if (m < a.M) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float gt = acc[mt][0][e];
-                        r[e] = gt / (1.0f + __expf(-gt)) * acc[mt][1][e];
+                for (int vq = 0; vq < 2; ++vq) {
+                    const int f = nt32 * 16 + 8 * vq + 4 * g2;
+                    if (f < a.ld_out) {
+                        float r[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float gt = acc[mt][4 * vq + e];
+                            r[e] = gt / (1.0f + __expf(-gt)) * acc[mt][4 * (vq + 2) + e];
+                        }
+                        uint2 v = make_uint2(pack_bf16x2(r[0], r[1]), pack_bf16x2(r[2], r[3]));
+                        *(uint2 *)(out + frag_offset(m, f, a.mt_total)) = v;
                     }
-                    uint2 v = make_uint2(pack_bf16x2(r[0], r[1]), pack_bf16x2(r[2], r[3]));
-                    *(uint2 *)(out + frag_offset(m, f, a.mt_total)) = v;
                 }
             }
         }

@@ -24,6 +24,7 @@ namespace sr {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 // Remember the text of the last failing HIP call for sr_strerror(SR_E_HIP).
 void note_hip_error(hipError_t e, const char *what);
