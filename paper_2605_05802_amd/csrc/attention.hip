@@ -22,6 +22,7 @@ namespace sr {
 namespace {
 
 constexpr float kNegBig = -1.0e30f;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 template <int D, int RT>
 __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a, AttnPhase p, int n_items) {
@@ -84,22 +85,57 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a, AttnPhase p, int 
     const size_t block_elems = (size_t)32 * D;
     const float scale_log2 = a.scale * 1.4426950408889634f;
 
-    for (int t0 = t_lo; t0 < t_hi; t0 += 32) {          // t_lo is a multiple of 32
+    // K and V of block i+1 are requested before block i is consumed, so one block's worth of loads
+    // (16 KiB per wavefront at d = 128) is always in flight.
+    bf16x8 kf[2][KS], vf[DT], kn[2][KS], vn[DT];
+    auto block_base = [&](int t0) -> size_t {
         const int page = pt[t0 / a.page_tokens];
         const int blk = (t0 % a.page_tokens) >> 5;
-        const size_t base = (((size_t)page * a.n_kv + kvh) * blocks_per_page + blk) * block_elems;
+        return (((size_t)page * a.n_kv + kvh) * blocks_per_page + blk) * block_elems;
+    };
+    constexpr bool kPrefetch = (RT == 1);               // two row tiles leave no registers for it
+    if (kPrefetch && t_lo < t_hi) {
+        const size_t base = block_base(t_lo);
         const uint16_t *kb = a.kpool + base, *vb = a.vpool + base;
-
-        bf16x8 kf[2][KS];
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks)
-                kf[tt][ks] = __builtin_bit_cast(bf16x8, *(const uint4 *)(kb + ((ks * 32 + tt * 16 + c) * 32 + 8 * g)));
-        bf16x8 vf[DT];
+                kn[tt][ks] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(kb + ((ks * 32 + tt * 16 + c) * 32 + 8 * g)));
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
-            vf[dt] = __builtin_bit_cast(bf16x8, *(const uint4 *)(vb + ((dt * 16 + c) * 32 + 8 * g)));
+            vn[dt] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(vb + ((dt * 16 + c) * 32 + 8 * g)));
+    }
+    for (int t0 = t_lo; t0 < t_hi; t0 += 32) {          // t_lo is a multiple of 32
+        if constexpr (kPrefetch) {
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) kf[tt][ks] = kn[tt][ks];
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) vf[dt] = vn[dt];
+        }
+        {
+            const int tn = (kPrefetch && t0 + 32 < t_hi) ? t0 + 32 : t0;   // last block: harmless re-read
+            const size_t base = block_base(tn);
+            const uint16_t *kb = a.kpool + base, *vb = a.vpool + base;
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks)
+                    kn[tt][ks] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(kb + ((ks * 32 + tt * 16 + c) * 32 + 8 * g)));
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+                vn[dt] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(vb + ((dt * 16 + c) * 32 + 8 * g)));
+        }
+        if constexpr (!kPrefetch) {
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) kf[tt][ks] = kn[tt][ks];
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) vf[dt] = vn[dt];
+        }
 
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
@@ -174,39 +210,56 @@ struct MergeArgs {
     uint16_t *out;
 };
 
-// One block per (query token, query head); thread = head dimension.
+// One block per (query token, query head); thread = head dimension.  The (max, sum) pairs of all
+// partial results are fetched first, one per thread, and turned into weights; the weighted sum of
+// the partial outputs then runs over independent loads in a fixed order.
+constexpr int kMaxMergeItems = 64;
+
 __global__ __launch_bounds__(128) void attn_merge_kernel(MergeArgs a) {
+    __shared__ float s_m[kMaxMergeItems], s_l[kMaxMergeItems], s_w[kMaxMergeItems];
+    __shared__ unsigned s_row[kMaxMergeItems];      // partial-result row of each item
     const int qt = blockIdx.x, h = blockIdx.y, dd = threadIdx.x;
-    if (dd >= a.d) return;
     const int n_rep = a.n_q / a.n_kv;
     const int kvh = h / n_rep, hr = h % n_rep;
+
+    int n_items = 0;
+    for (int ph = 0; ph < a.n_phases; ++ph) {
+        const AttnPhase &p = a.ph[ph];
+        const int unit = qt / p.q_per_unit, qi = qt % p.q_per_unit;
+        const int qtile = qi / p.q_per_item, row = (qi % p.q_per_item) * n_rep + hr;
+        const size_t item0 = (((size_t)unit * a.n_kv + kvh) * p.items_per_unit + qtile) * p.n_splits;
+        if (dd < p.n_splits) {
+            const size_t prow = (item0 + dd) * (16 * p.rt) + row;
+            const size_t base = (size_t)(p.part_o - a.ph[0].part_o) / a.d;   // phases share one buffer
+            s_row[n_items + dd] = (unsigned)(base + prow);
+            s_m[n_items + dd] = p.part_ml[prow * 2];
+            s_l[n_items + dd] = p.part_ml[prow * 2 + 1];
+        }
+        n_items += p.n_splits;
+    }
+    __syncthreads();
     float mbest = kNegBig;
-    for (int ph = 0; ph < a.n_phases; ++ph) {
-        const AttnPhase &p = a.ph[ph];
-        const int unit = qt / p.q_per_unit, qi = qt % p.q_per_unit;
-        const int qtile = qi / p.q_per_item, row = (qi % p.q_per_item) * n_rep + hr;
-        const size_t item0 = (((size_t)unit * a.n_kv + kvh) * p.items_per_unit + qtile) * p.n_splits;
-        for (int s = 0; s < p.n_splits; ++s) {
-            const size_t prow = (item0 + s) * (16 * p.rt) + row;
-            if (p.part_ml[prow * 2 + 1] > 0.f) mbest = fmaxf(mbest, p.part_ml[prow * 2]);
-        }
+    for (int i = 0; i < n_items; ++i)
+        if (s_l[i] > 0.f) mbest = fmaxf(mbest, s_m[i]);
+    float den = 0.f;
+    for (int i = 0; i < n_items; ++i) {
+        const float w = s_l[i] > 0.f ? exp2f(s_m[i] - mbest) : 0.f;
+        den += s_l[i] * w;
+        if (dd == 0) s_w[i] = w;
     }
-    float num = 0.f, den = 0.f;
-    for (int ph = 0; ph < a.n_phases; ++ph) {
-        const AttnPhase &p = a.ph[ph];
-        const int unit = qt / p.q_per_unit, qi = qt % p.q_per_unit;
-        const int qtile = qi / p.q_per_item, row = (qi % p.q_per_item) * n_rep + hr;
-        const size_t item0 = (((size_t)unit * a.n_kv + kvh) * p.items_per_unit + qtile) * p.n_splits;
-        for (int s = 0; s < p.n_splits; ++s) {
-            const size_t prow = (item0 + s) * (16 * p.rt) + row;
-            const float l = p.part_ml[prow * 2 + 1];
-            if (l > 0.f) {
-                const float w = exp2f(p.part_ml[prow * 2] - mbest);
-                den += l * w;
-                num += p.part_o[prow * a.d + dd] * w;
-            }
-        }
+    __syncthreads();
+    if (dd >= a.d) return;
+    const float *po = a.ph[0].part_o + dd;
+    float num = 0.f;
+    int i = 0;
+    for (; i + 4 <= n_items; i += 4) {
+        float v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = po[(size_t)s_row[i + u] * a.d];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) num += v[u] * s_w[i + u];
     }
+    for (; i < n_items; ++i) num += po[(size_t)s_row[i] * a.d] * s_w[i];
     const float r = den > 0.f ? num / den : 0.f;
     a.out[frag_offset(qt, h * a.d + dd, a.mt_total)] = f32_to_bf16(r);
 }
@@ -234,6 +287,9 @@ int launch_attn_merge(const AttnArgs &a, const AttnPhase *phases, int n_phases, 
                       int mt_total, hipStream_t stream) {
     if (n_qtok <= 0) return SR_OK;
     if (n_phases < 1 || n_phases > 2) return SR_E_ARG;
+    int total = 0;
+    for (int i = 0; i < n_phases; ++i) total += phases[i].n_splits;
+    if (total > kMaxMergeItems) return SR_E_ARG;
     MergeArgs m{};
     for (int i = 0; i < n_phases; ++i) m.ph[i] = phases[i];
     m.n_phases = n_phases;

@@ -50,8 +50,21 @@ __global__ __launch_bounds__(256) void resid_norm_kernel(NormArgs a) {
                 }
             } else {
                 f32x4 lo = *(const f32x4 *)(x + v * 8), hi = *(const f32x4 *)(x + v * 8 + 4);
-                for (int s = 0; s < a.n_partials; ++s) {
-                    const float *p = a.partials + (size_t)s * a.partial_stride + row * a.H + v * 8;
+                const float *p0 = a.partials + row * a.H + v * 8;
+                int s = 0;
+                for (; s + 4 <= a.n_partials; s += 4) {          // four independent loads in flight,
+                    f32x4 pl[4], ph[4];                          // added in split order
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const float *p = p0 + (size_t)(s + u) * a.partial_stride;
+                        pl[u] = *(const f32x4 *)p;
+                        ph[u] = *(const f32x4 *)(p + 4);
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) { lo += pl[u]; hi += ph[u]; }
+                }
+                for (; s < a.n_partials; ++s) {
+                    const float *p = p0 + (size_t)s * a.partial_stride;
                     lo += *(const f32x4 *)p;
                     hi += *(const f32x4 *)(p + 4);
                 }
@@ -105,10 +118,25 @@ __global__ __launch_bounds__(64) void qkv_post_kernel(QkvPostArgs a) {
     else { kind = 2; h = head - a.n_q - a.n_kv; col0 = q_cols + kv_cols + h * a.d; bias = a.bv ? a.bv + h * a.d : nullptr; }
 
     float lo = 0.f, hi = 0.f;
-    for (int s = 0; s < a.n_partials; ++s) {
-        const float *p = a.partials + (size_t)s * a.partial_stride + (size_t)m * a.ld + col0;
-        lo += p[i];
-        hi += p[i + half];
+    {
+        const float *p0 = a.partials + (size_t)m * a.ld + col0;
+        int s = 0;
+        for (; s + 4 <= a.n_partials; s += 4) {                  // independent loads, adds in split order
+            float pl[4], ph[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float *p = p0 + (size_t)(s + u) * a.partial_stride;
+                pl[u] = p[i];
+                ph[u] = p[i + half];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) { lo += pl[u]; hi += ph[u]; }
+        }
+        for (; s < a.n_partials; ++s) {
+            const float *p = p0 + (size_t)s * a.partial_stride;
+            lo += p[i];
+            hi += p[i + half];
+        }
     }
     if (bias) { lo += bf16_to_f32(bias[i]); hi += bf16_to_f32(bias[i + half]); }
     if (kind != 2) {

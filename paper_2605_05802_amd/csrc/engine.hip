@@ -319,7 +319,7 @@ int forward(sr_ctx *c, const Pass &p, hipStream_t st) {
             x.t_end = c->shared_tokens;
             x.causal_pos0 = ctx - 1;
             x.causal_stride = 0;
-            x.n_splits = ceil_div(c->shared_tokens, 128);
+            x.n_splits = ceil_div(c->shared_tokens, 64);
             if (x.n_splits > kMaxAttnSplits) x.n_splits = kMaxAttnSplits;
             x.split_tokens = round_up(ceil_div(c->shared_tokens, x.n_splits), 32);
             add_phase(x);
