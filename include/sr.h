@@ -199,8 +199,7 @@ typedef enum {
     SR_KC_NORM = 0,        /* residual add + RMSNorm (+ embedding gather) */
     SR_KC_GEMM_QKV,
     SR_KC_QKV_POST,        /* split-K sum + bias + RoPE + KV page write */
-    SR_KC_ATTN_SHARED,     /* decode attention over the prompt pages shared by a group */
-    SR_KC_ATTN_PRIVATE,    /* decode attention over each sequence's own pages */
+    SR_KC_ATTN_DECODE,     /* decode attention: shared-prompt phase and private phase in one launch */
     SR_KC_ATTN_PREFILL,
     SR_KC_ATTN_MERGE,
     SR_KC_GEMM_O,

@@ -19,7 +19,7 @@ EXPORTS = ("sr_init", "sr_destroy", "sr_load_weights", "sr_prefill_chunk", "sr_d
            "sr_retire_and_compact", "sr_gate_batch", "sr_set_actions", "sr_get_actions", "sr_get_logits",
            "sr_get_live_map", "sr_stats", "sr_strerror", "sr_profile", "sr_profile_read")
 
-KERNEL_CLASSES = ("norm", "gemm_qkv", "qkv_post", "attn_shared", "attn_private", "attn_prefill", "attn_merge",
+KERNEL_CLASSES = ("norm", "gemm_qkv", "qkv_post", "attn_decode", "attn_prefill", "attn_merge",
                   "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm_head", "argmax")
 
 

@@ -24,18 +24,26 @@ namespace {
 constexpr float kNegBig = -1.0e30f;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// One launch may cover two phases (decode: the shared-prompt phase followed by the private phase), so
+// that the short, narrow shared phase overlaps the private one instead of running alone.
 template <int D, int RT>
-__global__ __launch_bounds__(256) void attn_kernel(AttnArgs a, AttnPhase p, int n_items) {
+__global__ __launch_bounds__(256) void attn_kernel(AttnArgs a, AttnPhase p0, AttnPhase p1, int n0, int n_items) {
     constexpr int KS = D / 32;     // k-steps of the QK^T contraction
     constexpr int DT = D / 16;     // 16-wide tiles of the head dimension
     const int lane = threadIdx.x & 63;
-    const int item = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (item >= n_items) return;
+    // the wavefront index is uniform: tell the compiler, so that everything derived from the work item
+    // (phase, token range, page-table reads) lives in scalar registers
+    const int gitem = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    if (gitem >= n_items) return;
+    const bool second = gitem >= n0;
+    const AttnPhase &p = second ? p1 : p0;
+    const int item = second ? gitem - n0 : gitem;
 
-    // item -> (unit, kv head, q tile, split)
+    // item -> (unit, kv head, split, q tile): the q tiles of one split are neighbours, so the
+    // wavefronts of a workgroup that share K/V blocks fetch them at the same time
     int rest = item;
-    const int split = rest % p.n_splits; rest /= p.n_splits;
     const int qtile = rest % p.items_per_unit; rest /= p.items_per_unit;
+    const int split = rest % p.n_splits; rest /= p.n_splits;
     const int kvh = rest % a.n_kv;
     const int unit = rest / a.n_kv;
     const int n_rep = a.n_q / a.n_kv;
@@ -227,9 +235,9 @@ __global__ __launch_bounds__(128) void attn_merge_kernel(MergeArgs a) {
         const AttnPhase &p = a.ph[ph];
         const int unit = qt / p.q_per_unit, qi = qt % p.q_per_unit;
         const int qtile = qi / p.q_per_item, row = (qi % p.q_per_item) * n_rep + hr;
-        const size_t item0 = (((size_t)unit * a.n_kv + kvh) * p.items_per_unit + qtile) * p.n_splits;
+        const size_t item0 = ((size_t)unit * a.n_kv + kvh) * p.n_splits;
         if (dd < p.n_splits) {
-            const size_t prow = (item0 + dd) * (16 * p.rt) + row;
+            const size_t prow = ((item0 + dd) * p.items_per_unit + qtile) * (16 * p.rt) + row;
             const size_t base = (size_t)(p.part_o - a.ph[0].part_o) / a.d;   // phases share one buffer
             s_row[n_items + dd] = (unsigned)(base + prow);
             s_m[n_items + dd] = p.part_ml[prow * 2];
@@ -266,18 +274,28 @@ __global__ __launch_bounds__(128) void attn_merge_kernel(MergeArgs a) {
 
 }  // namespace
 
-int launch_attention(const AttnArgs &a, const AttnPhase &p, hipStream_t stream) {
-    const long long n_items = (long long)p.n_units * a.n_kv * p.items_per_unit * p.n_splits;
-    if (n_items <= 0 || p.t_end <= p.t_begin) return SR_OK;
-    if (n_items > 0x7FFFFFFF || (p.t_begin & 31) || (p.split_tokens & 31) || p.split_tokens <= 0) return SR_E_ARG;
+int launch_attention(const AttnArgs &a, const AttnPhase *phases, int n_phases, hipStream_t stream) {
+    if (n_phases < 1 || n_phases > 2) return SR_E_ARG;
+    long long n[2] = {0, 0};
     const int n_rep = a.n_q / a.n_kv;
-    if (p.q_per_item * n_rep > 16 * p.rt) return SR_E_ARG;
+    for (int i = 0; i < n_phases; ++i) {
+        const AttnPhase &p = phases[i];
+        n[i] = (long long)p.n_units * a.n_kv * p.items_per_unit * p.n_splits;
+        if (p.t_end <= p.t_begin) n[i] = 0;
+        if ((p.t_begin & 31) || (p.split_tokens & 31) || p.split_tokens <= 0 || p.q_per_item * n_rep > 16 * p.rt ||
+            p.rt != phases[0].rt)
+            return SR_E_ARG;
+    }
+    const long long n_items = n[0] + n[1];
+    if (n_items <= 0) return SR_OK;
+    if (n_items > 0x7FFFFFFF) return SR_E_ARG;
+    const AttnPhase &p0 = phases[0], &p1 = phases[n_phases - 1];
+    const int rt = p0.rt, n0 = (int)n[0], nt = (int)n_items;
     dim3 grid((unsigned)((n_items + 3) / 4)), block(256);
-    const int n = (int)n_items;
-    if (a.d == 128 && p.rt == 1) attn_kernel<128, 1><<<grid, block, 0, stream>>>(a, p, n);
-    else if (a.d == 128 && p.rt == 2) attn_kernel<128, 2><<<grid, block, 0, stream>>>(a, p, n);
-    else if (a.d == 64 && p.rt == 1) attn_kernel<64, 1><<<grid, block, 0, stream>>>(a, p, n);
-    else if (a.d == 64 && p.rt == 2) attn_kernel<64, 2><<<grid, block, 0, stream>>>(a, p, n);
+    if (a.d == 128 && rt == 1) attn_kernel<128, 1><<<grid, block, 0, stream>>>(a, p0, p1, n0, nt);
+    else if (a.d == 128 && rt == 2) attn_kernel<128, 2><<<grid, block, 0, stream>>>(a, p0, p1, n0, nt);
+    else if (a.d == 64 && rt == 1) attn_kernel<64, 1><<<grid, block, 0, stream>>>(a, p0, p1, n0, nt);
+    else if (a.d == 64 && rt == 2) attn_kernel<64, 2><<<grid, block, 0, stream>>>(a, p0, p1, n0, nt);
     else return SR_E_ARG;
     SR_HIP(hipGetLastError());
     return SR_OK;

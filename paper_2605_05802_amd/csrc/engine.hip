@@ -311,7 +311,7 @@ int forward(sr_ctx *c, const Pass &p, hipStream_t st) {
             AttnPhase x{};
             x.n_units = p.n_units / c->G;
             x.q_per_unit = c->G;
-            x.rt = (c->G * n_rep > 16) ? 2 : 1;
+            x.rt = n_rep > 16 ? 2 : 1;              // same row-tile count as the private phase: one launch
             x.q_per_item = (16 * x.rt) / n_rep < c->G ? (16 * x.rt) / n_rep : c->G;
             x.items_per_unit = ceil_div(c->G, x.q_per_item);
             x.pt_row_stride = c->G;
@@ -416,11 +416,8 @@ int forward(sr_ctx *c, const Pass &p, hipStream_t st) {
 
         aa.kpool = qa.kpool;
         aa.vpool = qa.vpool;
-        for (int i = 0; i < n_ph; ++i) {
-            const int kc = !p.decode ? SR_KC_ATTN_PREFILL : (ph[i].q_per_unit > 1 || ph[i].pt_row_stride > 1)
-                                                              ? SR_KC_ATTN_SHARED : SR_KC_ATTN_PRIVATE;
-            SR_TRY(timed(c, kc, st, [&] { return launch_attention(aa, ph[i], st); }));
-        }
+        SR_TRY(timed(c, p.decode ? SR_KC_ATTN_DECODE : SR_KC_ATTN_PREFILL, st,
+                     [&] { return launch_attention(aa, ph, n_ph, st); }));
         SR_TRY(timed(c, SR_KC_ATTN_MERGE, st,
                      [&] { return launch_attn_merge(aa, ph, n_ph, M, c->attn_out, c->mt_total, st); }));
 

@@ -183,7 +183,8 @@ struct AttnArgs {
     int pt_stride, page_tokens, n_q, n_kv, d;
     float scale;
 };
-int launch_attention(const AttnArgs &a, const AttnPhase &p, hipStream_t stream);
+// One launch over one or two phases (same rt); phases whose token range is empty contribute no work.
+int launch_attention(const AttnArgs &a, const AttnPhase *phases, int n_phases, hipStream_t stream);
 
 // Merge the partial results of up to two phases into out (fragment-major bf16 [query tokens][n_q*d]).
 // Query token qt belongs to unit qt / q_per_unit of each phase.
