@@ -94,6 +94,8 @@ def load(real: str = "double"):
         L.sro_argmax.restype = ci
         L.sro_argmax.argtypes = [vp, ci, ctypes.POINTER(cd)]
         L.sro_real_bytes.restype = ci
+        L.sro_set_bf16_contract.restype = None
+        L.sro_set_bf16_contract.argtypes = [ci]
         L.sro_rope_apply.restype = None
         L.sro_rope_apply.argtypes = [vp, ci, ci, cd]
         _LIBS[real] = L
@@ -206,6 +208,12 @@ class Seq:
         if rc:
             raise RuntimeError("oracle sequence capacity exceeded")
         return out
+
+
+def set_bf16_contract(on: bool, real: str = "double") -> None:
+    """Round activations to bf16 where a bf16 tensor-core implementation must (see sr_oracle.c).
+    Off by default; the exact evaluation is the reference, this mode only attributes error."""
+    load(real).sro_set_bf16_contract(int(on))
 
 
 def rope_apply(vec, pos: int, theta: float) -> np.ndarray:

@@ -153,6 +153,28 @@ typedef struct {
     real *v;
 } sro_seq;
 
+/*
+ * Optional "bf16 contract" mode (off by default): activations are rounded to bf16 (nearest even)
+ * at exactly the points where a bf16 tensor-core implementation must round them -- the inputs of
+ * every projection, the stored keys and values, the rotated queries and the softmax probabilities
+ * fed to the value product -- and nowhere else.  It separates the error that is inherent to bf16
+ * operands from implementation error: an implementation should agree with this mode far more
+ * closely than with the exact evaluation.
+ */
+static int g_contract = 0;
+void sro_set_bf16_contract(int on) { g_contract = on; }
+
+static inline real rb(real x) {
+    if (!g_contract) return x;
+    float f = (float)x;
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    u &= 0xFFFF0000u;
+    memcpy(&f, &u, 4);
+    return (real)f;
+}
+
 static inline real bf16_to_real(uint16_t b) {
     uint32_t u = (uint32_t)b << 16;
     float f;
@@ -222,7 +244,7 @@ static void rmsnorm(const real *x, const uint16_t *gain, real eps, real *y, int 
     real ss = 0;
     for (int i = 0; i < H; ++i) ss += x[i] * x[i];
     real inv = (real)1 / (real)sqrt((double)(ss / H + eps));
-    for (int i = 0; i < H; ++i) y[i] = x[i] * inv * bf16_to_real(gain[i]);
+    for (int i = 0; i < H; ++i) y[i] = rb(x[i] * inv * bf16_to_real(gain[i]));
 }
 
 /* Rotate-half RoPE on one head vector at absolute position pos:
@@ -276,6 +298,10 @@ int sro_forward_token(const sro_model *m, sro_seq *q, int32_t token, real *logit
         matvec(L->wv, s->qkv_bias ? L->bv : NULL, h, vnew, KD, H);
         for (int a = 0; a < nq; ++a) rope(qv + a * d, d, pos, s->rope_theta);
         for (int a = 0; a < nkv; ++a) rope(knew + a * d, d, pos, s->rope_theta);
+        if (g_contract) {
+            for (int i = 0; i < QD; ++i) qv[i] = rb(qv[i]);
+            for (int i = 0; i < KD; ++i) { knew[i] = rb(knew[i]); vnew[i] = rb(vnew[i]); }
+        }
 
         const real scale = (real)(1.0 / sqrt((double)d));
         for (int a = 0; a < nq; ++a) {
@@ -297,10 +323,12 @@ int sro_forward_token(const sro_model *m, sro_seq *q, int32_t token, real *logit
             real *oa = att + a * d;
             for (int i = 0; i < d; ++i) oa[i] = 0;
             for (int t = 0; t <= pos; ++t) {
-                const real p = sc[t] / den;
+                const real p = rb(sc[t]) / den;
                 const real *vt = vc + (size_t)t * KD + kvh * d;
                 for (int i = 0; i < d; ++i) oa[i] += p * vt[i];
             }
+            if (g_contract)
+                for (int i = 0; i < d; ++i) oa[i] = rb(oa[i]);
         }
         matvec(L->wo, NULL, att, proj, H, QD);
         for (int i = 0; i < H; ++i) x[i] += proj[i];
@@ -310,7 +338,7 @@ int sro_forward_token(const sro_model *m, sro_seq *q, int32_t token, real *logit
         matvec(L->wu, NULL, h, u, F, H);
         for (int i = 0; i < F; ++i) {
             real silu = g[i] / ((real)1 + (real)exp((double)-g[i]));
-            g[i] = silu * u[i];
+            g[i] = rb(silu * u[i]);
         }
         matvec(L->wd, NULL, g, proj, H, F);
         for (int i = 0; i < H; ++i) x[i] += proj[i];

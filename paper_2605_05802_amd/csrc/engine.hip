@@ -503,7 +503,7 @@ static int init_impl(sr_ctx *c) {
     c->ks_q = round_up(s.n_q_heads * d / 32, 16);
     c->ks_f = round_up(ceil_div(s.ffn, 32), 16);
     const int max_rows = o.max_prefill_rows > 0 ? o.max_prefill_rows : 8192;
-    c->R = round_up(max_rows > c->n_seq0 ? max_rows : c->n_seq0, 128);
+    c->R = round_up(max_rows > c->n_seq0 ? max_rows : c->n_seq0, 256);
     c->mt_total = c->R / 16;
 
     // RoPE tables, computed in double: angle = pos * theta^(-2i/d)

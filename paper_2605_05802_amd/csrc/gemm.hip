@@ -336,6 +336,177 @@ __global__ __launch_bounds__(kSkThreads, 2) void gemm_skinny_kernel(GemmArgs a) 
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Prefill (M > 128) kernel: compute bound, so the tile is sized for the matrix cores.
+//
+// An 8-wavefront workgroup owns a 256 x 256 output tile; wavefront (wn, wm) of the 4 x 2 arrangement
+// computes 64 features x 128 rows with 32x32x16 MFMAs (128 accumulator registers).  Both operands go
+// through LDS in 64-wide k stages (two k-steps, 32 KiB of W + 32 KiB of X per stage, double buffered),
+// so every byte crosses the vector-memory path once per workgroup: 128 flop per byte fetched, against
+// 64 for a 128 x 128 tile with W read straight into registers, which ran out of L1 bandwidth.
+// Fragments are read from LDS one k-half ahead of their MFMAs.
+// Workgroups are numbered so that the 32 that run together on one XCD form an 8 x 4 block of tiles
+// (2048 rows x 1024 features) whose operands they share through that XCD's L2.
+// ---------------------------------------------------------------------------------------------
+constexpr int kPfThreads = 512;
+constexpr int kPfStageVec = 4096;          // u32x4 per stage: [W: 2 k-steps x 16 tiles x 64][X: same]
+constexpr int kPfLdsBytes = 2 * kPfStageVec * 16;
+
+template <int EPI>
+__global__ __launch_bounds__(kPfThreads, 2) void gemm_prefill_kernel(GemmArgs a, int m_blocks, int n_blocks, int sm_count,
+                                                                     int st_count) {
+    extern __shared__ u32x4 pf_lds[];      // [2][kPfStageVec]
+
+    // linear id -> XCD -> supertile -> tile
+    const int L = blockIdx.x;
+    const int xcd = L & 7, jj = L >> 3;
+    const int w = jj & 31, sg = (jj >> 5) * 8 + xcd;
+    if (sg >= st_count) return;
+    const int mb = (sg % sm_count) * 8 + (w & 7);
+    const int nb = (sg / sm_count) * 4 + (w >> 3);
+    if (mb >= m_blocks || nb >= n_blocks) return;
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int wn = wave & 3, wm = wave >> 2;
+    const int r32 = lane & 31, g2 = lane >> 5;
+    const int sub = r32 >> 4, slot0 = (r32 & 15) + 16 * g2;
+
+    f32x16 acc[2][4];                      // [feature group of 32][row group of 32]
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    // staging: thread's r-th W vector is tile (tid + 512 r) / 128, k-step ((tid + 512 r) / 64) % 2
+    const u32x4 *wsrc[4];
+    int wdst[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int v = tid + kPfThreads * r, nt = v >> 7, kk = (v >> 6) & 1;
+        wsrc[r] = (const u32x4 *)a.W + ((size_t)(nb * 16 + nt) * a.ks_total + kk) * 64 + lane;
+        wdst[r] = (kk * 16 + nt) * 64 + lane;
+    }
+    // X: vector (tid + 512 r): k-step (tid + 512 r) / 1024, position within the 16 row tiles % 1024
+    const size_t x_ks_stride = (size_t)a.mt_total * 64;
+    const u32x4 *xsrc = (const u32x4 *)a.X + (size_t)mb * 16 * 64;
+    u32x4 stw[4], stx[4];
+    const int n_stages = a.ks_total / 2;
+
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int v = tid + kPfThreads * r;
+        stw[r] = wsrc[r][0];
+        stx[r] = xsrc[(size_t)(v >> 10) * x_ks_stride + (v & 1023)];
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        pf_lds[wdst[r]] = stw[r];
+        pf_lds[2048 + tid + kPfThreads * r] = stx[r];
+    }
+    __syncthreads();
+
+    // fragment offsets inside a stage: W group i of this wavefront, X group j
+    const int woff = (wn * 4 + sub) * 64 + slot0;          // + i * 128 (two tiles) + kk * 1024 + h * 32
+    const int xoff = 2048 + (wm * 8 + sub) * 64 + slot0;   // + j * 128 + kk * 1024 + h * 32
+
+    for (int st = 0; st < n_stages; ++st) {
+        const int buf = st & 1;
+        const int nxt = min(st + 1, n_stages - 1);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int v = tid + kPfThreads * r;
+            stw[r] = wsrc[r][(size_t)nxt * 2 * 64];
+            stx[r] = xsrc[(size_t)(nxt * 2 + (v >> 10)) * x_ks_stride + (v & 1023)];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        const u32x4 *base = pf_lds + buf * kPfStageVec;
+        bf16x8 wf[2][2], xf[2][4];         // [parity][group]
+#pragma unroll
+        for (int i = 0; i < 2; ++i) wf[0][i] = __builtin_bit_cast(bf16x8, base[woff + i * 128]);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) xf[0][j] = __builtin_bit_cast(bf16x8, base[xoff + j * 128]);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {      // q = k-step * 2 + k-half
+            __builtin_amdgcn_sched_barrier(0);
+            if (q + 1 < 4) {
+                const int o = ((q + 1) >> 1) * 1024 + ((q + 1) & 1) * 32;
+#pragma unroll
+                for (int i = 0; i < 2; ++i) wf[(q + 1) & 1][i] = __builtin_bit_cast(bf16x8, base[woff + i * 128 + o]);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) xf[(q + 1) & 1][j] = __builtin_bit_cast(bf16x8, base[xoff + j * 128 + o]);
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[q & 1][i], xf[q & 1][j], acc[i][j], 0, 0, 0);
+            if (q + 1 < 4) {
+#pragma unroll
+                for (int f = 0; f < 6; ++f) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 LDS read
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+            }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            pf_lds[(buf ^ 1) * kPfStageVec + wdst[r]] = stw[r];
+            pf_lds[(buf ^ 1) * kPfStageVec + 2048 + tid + kPfThreads * r] = stx[r];
+        }
+        __syncthreads();
+    }
+
+    // accumulator (i, j): lane (r32 = row within the 32-row group, g2) holds, in register v,
+    // feature 8 * (v / 4) + 4 * g2 + v % 4 of the 32-feature group
+    if constexpr (EPI == EPI_F32) {
+        float *out = (float *)a.out;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int m = mb * 256 + wm * 128 + j * 32 + r32;
+            if (m < a.M) {
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int vq = 0; vq < 4; ++vq) {
+                        const int n = nb * 256 + wn * 64 + i * 32 + 8 * vq + 4 * g2;
+                        if (n < a.N)
+                            *(f32x4 *)(out + (size_t)m * a.ld_out + n) =
+                                f32x4{acc[i][j][4 * vq], acc[i][j][4 * vq + 1], acc[i][j][4 * vq + 2], acc[i][j][4 * vq + 3]};
+                    }
+            }
+        }
+    } else {
+        uint16_t *out = (uint16_t *)a.out;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int m = mb * 256 + wm * 128 + j * 32 + r32;
+            if (m < a.M) {
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int vq = 0; vq < 2; ++vq) {
+                        const int f = nb * 128 + wn * 32 + i * 16 + 8 * vq + 4 * g2;
+                        if (f < a.ld_out) {
+                            float r[4];
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const float gt = acc[i][j][4 * vq + e];
+                                r[e] = gt / (1.0f + __expf(-gt)) * acc[i][j][4 * (vq + 2) + e];
+                            }
+                            uint2 v = make_uint2(pack_bf16x2(r[0], r[1]), pack_bf16x2(r[2], r[3]));
+                            *(uint2 *)(out + frag_offset(m, f, a.mt_total)) = v;
+                        }
+                    }
+            }
+        }
+    }
+}
+
 // One thread per 16-byte lane slot of the packed matrix.
 __global__ void pack_rows_kernel(const uint16_t *__restrict__ src, int n_rows, int K, uint16_t *__restrict__ dst,
                                  int ks_total, int dst_row0, int interleave16, int which) {
@@ -375,6 +546,28 @@ int launch_gemm(const GemmArgs &a, GemmEpilogue epi, hipStream_t stream) {
         dim3 sgrid(ceil_div(a.N, kSkBN), 1, epi == EPI_F32 ? a.splits : 1), sblock(kSkThreads);
         if (epi == EPI_F32) gemm_skinny_kernel<EPI_F32><<<sgrid, sblock, 0, stream>>>(a);
         else gemm_skinny_kernel<EPI_SWIGLU><<<sgrid, sblock, 0, stream>>>(a);
+        SR_HIP(hipGetLastError());
+        return SR_OK;
+    }
+    // wide outputs only: for N of a few thousand the 256 x 256 tiles leave too few workgroups per round
+    if (m_blocks > 1 && a.N >= 16384) {
+        const int mb256 = ceil_div(a.M, 256), nb256 = ceil_div(a.N, 256);
+        if (mb256 * 16 > a.mt_total || a.splits != 1) return SR_E_ARG;
+        static bool attr_set = false;
+        if (!attr_set) {
+            SR_HIP(hipFuncSetAttribute((const void *)gemm_prefill_kernel<EPI_F32>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kPfLdsBytes));
+            SR_HIP(hipFuncSetAttribute((const void *)gemm_prefill_kernel<EPI_SWIGLU>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kPfLdsBytes));
+            attr_set = true;
+        }
+        const int sm_count = ceil_div(mb256, 8), sn_count = ceil_div(nb256, 4);
+        const int st_count = sm_count * sn_count;
+        dim3 pgrid((unsigned)(ceil_div(st_count, 8) * 8 * 32)), pblock(kPfThreads);
+        if (epi == EPI_F32)
+            gemm_prefill_kernel<EPI_F32><<<pgrid, pblock, kPfLdsBytes, stream>>>(a, mb256, nb256, sm_count, st_count);
+        else
+            gemm_prefill_kernel<EPI_SWIGLU><<<pgrid, pblock, kPfLdsBytes, stream>>>(a, mb256, nb256, sm_count, st_count);
         SR_HIP(hipGetLastError());
         return SR_OK;
     }

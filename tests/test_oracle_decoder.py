@@ -153,3 +153,20 @@ def test_episode_accounting_and_identical_groups():
     n_seq = cfg.n_groups * cfg.G
     assert rec["decoded_tokens"] == round(n_seq * cfg.act_len * (cfg.turns - f * (cfg.turns - 2)))
     assert rec["final_live_groups"] == [g for g in range(cfg.n_groups) if not gate["cut"][g]]
+
+
+def test_bf16_contract_mode_is_off_by_default_and_small(small):
+    """The contract mode only rounds activations to bf16: it must stay close to the exact evaluation
+    (relative 2^-9 roundings) and must not leak into later exact evaluations."""
+    tokens = synth.uniform_ids(12, 3, 55, SMALL.vocab)
+    m = oracle.Model(small)
+    exact = m.new_seq(32).forward(tokens)
+    oracle.set_bf16_contract(True)
+    try:
+        rounded = m.new_seq(32).forward(tokens)
+    finally:
+        oracle.set_bf16_contract(False)
+    again = m.new_seq(32).forward(tokens)
+    assert np.array_equal(exact, again)
+    d = np.abs(rounded - exact).max()
+    assert 0 < d < 0.05 * np.abs(exact).max()
