@@ -152,7 +152,9 @@ int pick_splits(int M, int N, int ks_total) {
 int alloc_packed(sr_ctx *c, PackedMat *m, int n_rows, int K, hipStream_t st) {
     m->N = n_rows;
     m->ks = round_up(ceil_div(K, 32), 16);       // the GEMMs consume k-steps in groups of 16
-    const size_t elems = (size_t)round_up(n_rows, 256) * m->ks * 32;
+    // row padding covers both workgroup widths of the decode kernels (256 and 160 features)
+    const int rows = round_up(n_rows, 256) > round_up(n_rows, 160) ? round_up(n_rows, 256) : round_up(n_rows, 160);
+    const size_t elems = (size_t)rows * m->ks * 32;
     SR_TRY(dev_alloc(c, &m->p, elems));
     SR_HIP(hipMemsetAsync(m->p, 0, elems * 2, st));
     return SR_OK;
@@ -266,7 +268,9 @@ int gemm(sr_ctx *c, const uint4 *X, const PackedMat &W, int M, GemmEpilogue epi,
     a.out = out;
     a.ld_out = ld_out;
     a.splits = 1;
-    a.wide = use_wide(M, W.N, W.ks) ? 1 : 0;
+    // gate|up (37 888 packed rows at the 7B shape) splits into 237 workgroups of 160 features, which
+    // covers the 256 CUs better than 148 of 256; the other wide matrices prefer 256-feature workgroups
+    a.wide = use_wide(M, W.N, W.ks) ? (epi == EPI_SWIGLU ? 5 : 8) : 0;
     if (epi == EPI_F32 && splits_out) {
         a.splits = pick_splits(M, W.N, W.ks);
         a.split_stride = (size_t)round_up(M, 128) * ld_out;

@@ -179,21 +179,26 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
 // (16 KiB per wavefront) stay in flight across every barrier.  No branch in the loop body: the
 // compiler counts outstanding loads exactly.
 // ---------------------------------------------------------------------------------------------
-constexpr int kSkThreads = 512;
+// Workgroup width is a template parameter: 8 wavefronts (256 features) or 5 (160 features).  With
+// one workgroup per CU the per-CU rate bounds the kernel, so a matrix should break into roughly 256
+// equal workgroups: 37 888 packed gate|up rows give 148 workgroups of 256 features (108 CUs idle)
+// but 237 of 160.
 #ifndef SK_PF
 #define SK_PF 8
 #endif
 constexpr int kSkPF = SK_PF;            // k-steps of W in registers per wavefront (ring depth)
-constexpr int kSkBN = 256;
-constexpr int kSkXR = kChunkVec / kSkThreads;   // X vectors per thread per chunk (4)
 
 // The MFMA used here is the 32x32x16 form: with one workgroup per CU all eight wavefronts stall at
 // the same barriers, and a single wavefront keeps the matrix pipe far busier with 32x32 tiles than
 // with 16x16 ones.  Its operands (32 rows x 16 k) are assembled from the same 16-row fragment layout
 // by addressing: lane (r = lane % 32, g = lane / 32) of k-half h takes the 16 bytes of row tile r / 16,
 // lane slot (r % 16) + 16 * (2h + g).
-template <int EPI>
-__global__ __launch_bounds__(kSkThreads, 2) void gemm_skinny_kernel(GemmArgs a) {
+template <int EPI, int WAVES>
+__global__ __launch_bounds__(64 * WAVES, 2) void gemm_skinny_kernel(GemmArgs a) {
+    constexpr int kSkThreads = 64 * WAVES;
+    // X vectors per thread per chunk; when the chunk does not divide evenly the surplus slots re-copy
+    // vectors that another thread also copies (same data to the same place), keeping the loop branch-free
+    constexpr int kSkXR = (kChunkVec + kSkThreads - 1) / kSkThreads;
     __shared__ u32x4 lds[2][kChunkVec];   // 2 x 32 KiB
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
@@ -202,7 +207,7 @@ __global__ __launch_bounds__(kSkThreads, 2) void gemm_skinny_kernel(GemmArgs a) 
     const int units_per_split = ceil_div(units, a.splits);
     const int ks0 = sp * units_per_split * kSkPF;
     const int ks1 = min(ks0 + units_per_split * kSkPF, a.ks_total);
-    const int nt32 = nb * 8 + wave;                 // this wavefront's 32 output features
+    const int nt32 = nb * WAVES + wave;             // this wavefront's 32 output features
     const int r32 = lane & 31, g2 = lane >> 5;
     const int sub = r32 >> 4;                       // which 16-row tile of the pair
     const int slot0 = (r32 & 15) + 16 * g2;         // lane slot for k-half 0; k-half 1 is +32
@@ -217,9 +222,17 @@ __global__ __launch_bounds__(kSkThreads, 2) void gemm_skinny_kernel(GemmArgs a) 
         const u32x4 *wp0 = (const u32x4 *)a.W + ((size_t)(nt32 * 2 + sub) * a.ks_total) * 64 + slot0;
         const u32x4 *wp1 = wp0 + 32;
         const int last = ks1 - 1;
-        // thread's r-th vector of a chunk: chunk index tid + 512 r -> k-step r, position tid
-        const u32x4 *xp = (const u32x4 *)a.X + tid;
+        // thread's r-th vector of a chunk has chunk index (tid + threads * r) % 2048:
+        // k-step index / 512, position index % 512
+        const u32x4 *xp = (const u32x4 *)a.X;
         const size_t x_ks_stride = (size_t)a.mt_total * 64;
+        int xkk[kSkXR], xpos[kSkXR], xidx[kSkXR];
+#pragma unroll
+        for (int r = 0; r < kSkXR; ++r) {
+            xidx[r] = (tid + kSkThreads * r) % kChunkVec;
+            xkk[r] = xidx[r] >> 9;
+            xpos[r] = xidx[r] & 511;
+        }
         const int xoff = sub * 64 + slot0;          // + mt32 * 128 + h * 32 inside a k-step of a buffer
 
         u32x4 w0[kSkPF], w1[kSkPF], xr[2][kSkXR];
@@ -229,11 +242,11 @@ __global__ __launch_bounds__(kSkThreads, 2) void gemm_skinny_kernel(GemmArgs a) 
             w1[i] = wp1[(size_t)(ks0 + i) * 64];
         }
 #pragma unroll
-        for (int r = 0; r < kSkXR; ++r) xr[0][r] = xp[(size_t)(ks0 + r) * x_ks_stride];
+        for (int r = 0; r < kSkXR; ++r) xr[0][r] = xp[(size_t)(ks0 + xkk[r]) * x_ks_stride + xpos[r]];
 #pragma unroll
-        for (int r = 0; r < kSkXR; ++r) xr[1][r] = xp[(size_t)min(ks0 + kKC + r, last) * x_ks_stride];
+        for (int r = 0; r < kSkXR; ++r) xr[1][r] = xp[(size_t)min(ks0 + kKC + xkk[r], last) * x_ks_stride + xpos[r]];
 #pragma unroll
-        for (int r = 0; r < kSkXR; ++r) lds[0][tid + kSkThreads * r] = xr[0][r];
+        for (int r = 0; r < kSkXR; ++r) lds[0][xidx[r]] = xr[0][r];
         __syncthreads();
 
         for (int ks = ks0; ks < ks1; ks += kSkPF) {
@@ -244,7 +257,7 @@ __global__ __launch_bounds__(kSkThreads, 2) void gemm_skinny_kernel(GemmArgs a) 
                 __builtin_amdgcn_sched_barrier(0);               // keep the issue order = deadline order
 #pragma unroll
                 for (int r = 0; r < kSkXR; ++r)                  // X two chunks ahead
-                    xr[half][r] = xp[(size_t)min(kc0 + 2 * kKC + r, last) * x_ks_stride];
+                    xr[half][r] = xp[(size_t)min(kc0 + 2 * kKC + xkk[r], last) * x_ks_stride + xpos[r]];
                 __builtin_amdgcn_sched_barrier(0);
                 // X fragments are fetched from LDS one k-step ahead of the MFMAs that use them and the
                 // two instruction streams are interleaved explicitly.
@@ -287,7 +300,7 @@ __global__ __launch_bounds__(kSkThreads, 2) void gemm_skinny_kernel(GemmArgs a) 
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int r = 0; r < kSkXR; ++r)                  // X for the next chunk (fetched a chunk ago)
-                    lds[half ^ 1][tid + kSkThreads * r] = xr[half ^ 1][r];
+                    lds[half ^ 1][xidx[r]] = xr[half ^ 1][r];
                 __syncthreads();
             }
         }
@@ -543,9 +556,15 @@ int launch_gemm(const GemmArgs &a, GemmEpilogue epi, hipStream_t stream) {
     if (m_blocks * 8 > a.mt_total || a.splits < 1 || m_blocks > 65535 || a.splits > 65535 || a.ks_total % 16)
         return SR_E_ARG;
     if (m_blocks == 1 && a.wide) {
-        dim3 sgrid(ceil_div(a.N, kSkBN), 1, epi == EPI_F32 ? a.splits : 1), sblock(kSkThreads);
-        if (epi == EPI_F32) gemm_skinny_kernel<EPI_F32><<<sgrid, sblock, 0, stream>>>(a);
-        else gemm_skinny_kernel<EPI_SWIGLU><<<sgrid, sblock, 0, stream>>>(a);
+        const int waves = a.wide == 5 ? 5 : 8;
+        dim3 sgrid(ceil_div(a.N, 32 * waves), 1, epi == EPI_F32 ? a.splits : 1), sblock(64 * waves);
+        if (waves == 5) {
+            if (epi == EPI_F32) gemm_skinny_kernel<EPI_F32, 5><<<sgrid, sblock, 0, stream>>>(a);
+            else gemm_skinny_kernel<EPI_SWIGLU, 5><<<sgrid, sblock, 0, stream>>>(a);
+        } else {
+            if (epi == EPI_F32) gemm_skinny_kernel<EPI_F32, 8><<<sgrid, sblock, 0, stream>>>(a);
+            else gemm_skinny_kernel<EPI_SWIGLU, 8><<<sgrid, sblock, 0, stream>>>(a);
+        }
         SR_HIP(hipGetLastError());
         return SR_OK;
     }

@@ -102,7 +102,7 @@ struct GemmArgs {
     int mt_total;        // row tiles in X (and in a fragment-major output)
     int ks_total;        // k-steps (K padded to 32) in X and W
     int splits;          // split-K factor (EPI_F32 only)
-    int wide;            // M <= 128 only: 1 = 8-wavefront workgroups of 256 features, 0 = 4 wavefronts of 128
+    int wide;            // M <= 128 only: 8 or 5 = wavefronts per workgroup (32 features each), 0 = 4 wavefronts of 128 features
     void *out;
     int ld_out;          // EPI_F32: row stride (elements); EPI_SWIGLU: k-steps*32 of the output matrix
     size_t split_stride; // EPI_F32: elements between consecutive splits
