@@ -323,7 +323,7 @@ int forward(sr_ctx *c, const Pass &p, hipStream_t st) {
             x.t_end = c->shared_tokens;
             x.causal_pos0 = ctx - 1;
             x.causal_stride = 0;
-            x.n_splits = ceil_div(c->shared_tokens, 64);
+            x.n_splits = ceil_div(c->shared_tokens, 256);
             if (x.n_splits > kMaxAttnSplits) x.n_splits = kMaxAttnSplits;
             x.split_tokens = round_up(ceil_div(c->shared_tokens, x.n_splits), 32);
             add_phase(x);
@@ -340,7 +340,11 @@ int forward(sr_ctx *c, const Pass &p, hipStream_t st) {
         y.causal_pos0 = ctx - 1;
         y.causal_stride = 0;
         const int priv = ctx - c->shared_tokens;
-        y.n_splits = ceil_div(priv, 256);
+        // about 2048 wavefronts (8 per CU) in the private phase, each at least 128 tokens long; a function
+        // of the context length and the batch shape only, never of the row
+        y.n_splits = 2048 / (p.n_units * s.n_kv_heads);
+        if (y.n_splits > ceil_div(priv, 128)) y.n_splits = ceil_div(priv, 128);
+        if (y.n_splits < 1) y.n_splits = 1;
         if (y.n_splits > kMaxAttnSplits) y.n_splits = kMaxAttnSplits;
         y.split_tokens = round_up(ceil_div(priv, y.n_splits), 32);
         add_phase(y);
