@@ -326,3 +326,25 @@ def test_7b_shape_sampled_sequences():
           f"mean {con_mean:.3e}; token mismatches {mism}")
     ctx.close()
     assert gpu_max <= 2.0 * con_max and gpu_mean <= 2.0 * con_mean and mism == 0
+
+
+def test_group_size_16_with_two_gate_turns():
+    """G = 16 (120 pairs per group), gates after turns 2 and 4 at threshold 0.25: a group that survives
+    the first gate can still be retired by the second; each gate sees only the then-live groups."""
+    shape = synth.ModelShape(2, 256, 4, 2, 64, 512, 512)
+    cfg = synth.EpisodeConfig("g16", 5, 16, 64, 5, 12, 3, 8, (2, 4), 0.25, 0.4)
+    rec, stats, worst, mism, near = run_and_compare(shape, cfg, seed=21, page_tokens=32)
+    assert worst <= LOGIT_TOL and mism == 0
+    assert set(rec["gate"].keys()) == {2, 4}
+    assert len(rec["gate"][4]["sums"]) == len(rec["live_groups"][3])
+    assert stats["groups_retired"] == 5 - len(rec["final_live_groups"])
+
+
+def test_batch_larger_than_one_row_block():
+    """160 live sequences: the decode batch spans two 128-row blocks, so the decode projections take the
+    multi-block kernels; after the gate the batch shrinks below 128 rows and switches kernels mid-episode."""
+    shape = synth.ModelShape(1, 256, 4, 2, 64, 512, 512)
+    cfg = synth.EpisodeConfig("m160", 20, 8, 32, 3, 8, 2, 16, (2,), 0.3, 0.5)
+    rec, stats, worst, mism, near = run_and_compare(shape, cfg, seed=22, page_tokens=32)
+    assert worst <= LOGIT_TOL and mism == 0
+    assert stats["n_live_seq"] == 8 * len(rec["final_live_groups"]) < 128
