@@ -63,6 +63,13 @@ typedef struct {
                                 0 = the host supplies action ids with sr_set_actions */
     int32_t max_prefill_rows;/* rows (sequences x chunk tokens) processed per prefill pass; 0 = default 8192 */
     uint64_t kv_pool_bytes;  /* size of the KV page pool (K and V, all layers) */
+    float temperature;       /* 0 = greedy decoding; > 0 = sample from softmax(logits / temperature) (the paper's
+                                rollouts use 0.7, Section 3.1) by the Gumbel-max rule:
+                                token = argmax_v (logit_v / T - ln(-ln(u_v))), lowest index on ties, with
+                                u_v = (top 23 bits of SplitMix64(key, counter v) + 0.5) / 2^23 and key derived from
+                                (sample_seed, original sequence id, position of the token): reproducible, and
+                                independent of where the sequence sits in the batch */
+    uint64_t sample_seed;
 } sr_options;
 
 /* bf16 device pointers; borrowed only for the duration of sr_load_weights. */
@@ -128,9 +135,10 @@ int sr_prefill_chunk(sr_ctx *ctx, const int32_t *tokens, int chunk_len, int shar
 
 /*
  * Decode one token for every live sequence: pick token = forced[r] if forced != NULL, else
- * the greedy choice (largest current logit, lowest index on ties); append it and compute
- * the logits that follow it.  out_tokens (device int32 [n_live_seq], may be NULL) always
- * receives the greedy choice, also under forcing.  On the first decode step after a
+ * the library's own choice -- greedy (largest current logit, lowest index on ties) or, with
+ * temperature > 0, the sampled token; append it and compute the logits that follow it.
+ * out_tokens (device int32 [n_live_seq], may be NULL) always receives the library's own
+ * choice, also under forcing.  On the first decode step after a
  * per-sequence prefill the turn's action id (token % action_mod, from the token actually
  * appended) is recorded in the action table.
  * SR_E_STATE before any prefill; SR_E_ARG when max_seq_len would be exceeded; SR_E_NOMEM

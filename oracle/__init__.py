@@ -93,6 +93,8 @@ def load(real: str = "double"):
         L.sro_forward.argtypes = [vp, vp, vp, ci, vp]
         L.sro_argmax.restype = ci
         L.sro_argmax.argtypes = [vp, ci, ctypes.POINTER(cd)]
+        L.sro_sample.restype = ci
+        L.sro_sample.argtypes = [vp, ci, cd, ctypes.c_uint64, ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(cd)]
         L.sro_real_bytes.restype = ci
         L.sro_set_bf16_contract.restype = None
         L.sro_set_bf16_contract.argtypes = [ci]
@@ -232,16 +234,27 @@ def argmax(logits):
     return idx, gap.value
 
 
+def sample(logits, temperature: float, seed: int, orig_seq: int, pos: int):
+    """(token drawn from softmax(logits / T) by the Gumbel-max rule with counter-based uniforms keyed
+    (seed, original sequence id, position); gap between the best and second-best perturbed score)."""
+    lg = np.ascontiguousarray(logits)
+    L = load("double" if lg.dtype == np.float64 else "float")
+    gap = ctypes.c_double()
+    idx = L.sro_sample(lg.ctypes.data, len(lg), temperature, seed, orig_seq, pos, ctypes.byref(gap))
+    return idx, gap.value
+
+
 # ----------------------------------------------------------------------------
-# gated group rollout (Appendix C.1), greedy decoding
+# gated group rollout (Appendix C.1)
 # ----------------------------------------------------------------------------
 def run_episode(model: Model, prompts, obs_fn, G: int, turns: int, act_len: int, action_mod: int,
-                gate_turns, d_L: float, keep_logits: bool = False):
+                gate_turns, d_L: float, keep_logits: bool = False, temperature: float = 0.0, sample_seed: int = 0):
     """Rolls every group forward turn by turn, gating at the given turns.
 
     prompts: int32 [n_groups, P] (shared by the G members of a group).
     obs_fn(turn) -> int32 [n_groups*G, obs_len] rows in ORIGINAL (group-major) order.
-    Each turn appends the observation chunk, then decodes act_len tokens greedily; the
+    Each turn appends the observation chunk, then decodes act_len tokens (greedily, or sampled at
+    `temperature` > 0 with `sample` keyed by the sequence's original id and its current length); the
     turn's action id is (first decoded token) mod action_mod.  After a gate turn K the
     pairwise-distance sum S_K over the first K actions is compared with gate_bound and
     groups with S_K < bound stop there and leave the batch.
@@ -276,7 +289,10 @@ def run_episode(model: Model, prompts, obs_fn, G: int, turns: int, act_len: int,
             if keep_logits:
                 t_log.append({r: logits[r].copy() for r in rows})
             for r in rows:
-                tok, gap = argmax(logits[r])
+                if temperature > 0:
+                    tok, gap = sample(logits[r], temperature, sample_seed, r, len(seqs[r]))
+                else:
+                    tok, gap = argmax(logits[r])
                 t_tok[a, r], t_gap[a, r] = tok, gap
                 if a == 0:
                     actions[r, turn] = tok % action_mod

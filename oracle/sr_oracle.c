@@ -362,6 +362,37 @@ int sro_forward(const sro_model *m, sro_seq *q, const int32_t *tokens, int n, re
     return 0;
 }
 
+/*
+ * Temperature sampling (the paper's rollouts are sampled at T = 0.7, Section 3.1) by the Gumbel-max
+ * rule: token = argmax_v (logit_v / T + g_v) with g_v = -ln(-ln(u_v)) independent standard Gumbel
+ * variates, which draws exactly from softmax(logits / T).  The uniforms come from SplitMix64 used
+ * counter-based: stream key from (seed, original sequence id, position), counter = vocabulary index,
+ * u = (top 23 bits + 0.5) / 2^23.  Lowest index on ties; also reports the gap to the runner-up score.
+ */
+static uint64_t smx_finalize(uint64_t z) {
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+    return z ^ (z >> 31);
+}
+
+int sro_sample(const real *logits, int V, double temperature, uint64_t seed, int32_t orig_seq, int32_t pos,
+               double *top2_gap) {
+    const uint64_t golden = 0x9E3779B97F4A7C15ULL;
+    const uint64_t stream = ((uint64_t)(uint32_t)orig_seq << 32) | (uint32_t)pos;
+    const uint64_t key = smx_finalize(smx_finalize(seed + golden) ^ (stream * 0xD1342543DE82EF95ULL + 1ULL));
+    int best = 0;
+    double best_s = -INFINITY, second = -INFINITY;
+    for (int v = 0; v < V; ++v) {
+        const uint64_t r = smx_finalize(key + ((uint64_t)v + 1ULL) * golden);
+        const double u = ((double)(r >> 41) + 0.5) / 8388608.0;
+        const double sc = (double)logits[v] / temperature - log(-log(u));
+        if (sc > best_s) { second = best_s; best_s = sc; best = v; }
+        else if (sc > second) second = sc;
+    }
+    if (top2_gap) *top2_gap = best_s - second;
+    return best;
+}
+
 /* Greedy choice: lowest index among the maxima.  Also reports the gap to the runner-up. */
 int sro_argmax(const real *logits, int V, double *top2_gap) {
     int best = 0;

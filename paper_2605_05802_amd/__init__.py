@@ -39,7 +39,8 @@ class ModelShape(ctypes.Structure):
 class Options(ctypes.Structure):
     _fields_ = [("page_tokens", ctypes.c_int32), ("max_seq_len", ctypes.c_int32), ("max_turns", ctypes.c_int32),
                 ("action_mod", ctypes.c_int32), ("max_prefill_rows", ctypes.c_int32),
-                ("kv_pool_bytes", ctypes.c_uint64)]
+                ("kv_pool_bytes", ctypes.c_uint64), ("temperature", ctypes.c_float),
+                ("sample_seed", ctypes.c_uint64)]
 
 
 class LayerWeights(ctypes.Structure):
@@ -136,10 +137,12 @@ class Context:
     """Owns one sr_ctx.  Methods mirror the C entry points one to one."""
 
     def __init__(self, shape, n_groups: int, G: int, threshold: float, *, page_tokens=64, max_seq_len=4096,
-                 max_turns=32, action_mod=64, max_prefill_rows=0, kv_pool_bytes=1 << 30):
+                 max_turns=32, action_mod=64, max_prefill_rows=0, kv_pool_bytes=1 << 30, temperature=0.0,
+                 sample_seed=0):
         self.shape = ModelShape(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
                                 shape.ffn, shape.vocab, shape.rms_eps, shape.rope_theta, int(shape.qkv_bias))
-        self.opt = Options(page_tokens, max_seq_len, max_turns, action_mod, max_prefill_rows, kv_pool_bytes)
+        self.opt = Options(page_tokens, max_seq_len, max_turns, action_mod, max_prefill_rows, kv_pool_bytes,
+                           temperature, sample_seed)
         self.G, self.n_groups0, self.vocab, self.max_turns = G, n_groups, shape.vocab, max_turns
         self._h = ctypes.c_void_p()
         _check(lib().sr_init(ctypes.byref(self._h), ctypes.byref(self.shape), n_groups, G, threshold,

@@ -174,22 +174,43 @@ __device__ __forceinline__ MaxIdx better(MaxIdx a, MaxIdx b) {
     return (b.v > a.v || (b.v == a.v && b.i < a.i)) ? b : a;
 }
 
+__device__ __forceinline__ uint64_t smx_finalize(uint64_t z) {
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+    return z ^ (z >> 31);
+}
+
 // One 1024-thread block per row: strided scan, wavefront shuffle reduction, then 16 wave results.
+// With inv_temperature > 0 every logit is scaled and perturbed by a standard Gumbel variate drawn from a
+// counter-based SplitMix64 stream keyed (seed, original sequence id, position), counter = vocabulary
+// index: the argmax of the perturbed scores is a draw from softmax(logits / T).
 __global__ __launch_bounds__(1024) void argmax_kernel(const float *__restrict__ logits, int vocab,
                                                       const int32_t *__restrict__ forced, int32_t *greedy_out,
                                                       int32_t *chosen, int32_t *actions, int max_turns,
-                                                      int turn_idx, int action_mod) {
+                                                      int turn_idx, int action_mod, float inv_temperature,
+                                                      uint64_t seed, const int32_t *__restrict__ orig_seq, int pos) {
     __shared__ MaxIdx s_best[16];
     const int r = blockIdx.x;
     const float *row = logits + (size_t)r * vocab;
     MaxIdx best{-INFINITY, 0x7FFFFFFF};
     const int nvec = vocab >> 2;
-    for (int v = threadIdx.x; v < nvec; v += 1024) {
-        const f32x4 x = *(const f32x4 *)(row + v * 4);
+    if (inv_temperature > 0.f) {
+        const uint64_t golden = 0x9E3779B97F4A7C15ULL;
+        const uint64_t stream = ((uint64_t)(uint32_t)orig_seq[r] << 32) | (uint32_t)pos;
+        const uint64_t key = smx_finalize(smx_finalize(seed + golden) ^ (stream * 0xD1342543DE82EF95ULL + 1ULL));
+        for (int v = threadIdx.x; v < vocab; v += 1024) {
+            const uint64_t rnd = smx_finalize(key + ((uint64_t)v + 1ULL) * golden);
+            const float u = ((float)(uint32_t)(rnd >> 41) + 0.5f) * (1.0f / 8388608.0f);
+            best = better(best, MaxIdx{row[v] * inv_temperature - logf(-logf(u)), v});
+        }
+    } else {
+        for (int v = threadIdx.x; v < nvec; v += 1024) {
+            const f32x4 x = *(const f32x4 *)(row + v * 4);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) best = better(best, MaxIdx{x[e], v * 4 + e});
+            for (int e = 0; e < 4; ++e) best = better(best, MaxIdx{x[e], v * 4 + e});
+        }
+        for (int v = nvec * 4 + threadIdx.x; v < vocab; v += 1024) best = better(best, MaxIdx{row[v], v});
     }
-    for (int v = nvec * 4 + threadIdx.x; v < vocab; v += 1024) best = better(best, MaxIdx{row[v], v});
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) {
         MaxIdx o{__shfl_xor(best.v, off, 64), __shfl_xor(best.i, off, 64)};
@@ -250,10 +271,11 @@ int launch_qkv_post(const QkvPostArgs &a, hipStream_t stream) {
 
 int launch_argmax(const float *logits, int rows, int vocab, const int32_t *forced, int32_t *greedy_out,
                   int32_t *chosen, int32_t *actions, int max_turns, int turn_idx, int action_mod,
-                  hipStream_t stream) {
+                  float inv_temperature, uint64_t seed, const int32_t *orig_seq, int pos, hipStream_t stream) {
     if (rows <= 0) return SR_OK;
     argmax_kernel<<<dim3(rows), dim3(1024), 0, stream>>>(logits, vocab, forced, greedy_out, chosen, actions,
-                                                         max_turns, turn_idx, action_mod);
+                                                         max_turns, turn_idx, action_mod, inv_temperature, seed,
+                                                         orig_seq, pos);
     SR_HIP(hipGetLastError());
     return SR_OK;
 }

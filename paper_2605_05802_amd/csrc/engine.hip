@@ -71,6 +71,7 @@ struct sr_ctx {
     // device batch state
     int32_t *d_pt = nullptr;
     int32_t *d_actions[2] = {nullptr, nullptr};
+    int32_t *d_orig[2] = {nullptr, nullptr};   // original sequence id of every live row (keys the sampler)
     float *d_logits[2] = {nullptr, nullptr};
     int cur = 0;
     int32_t *d_greedy = nullptr, *d_chosen = nullptr, *d_sums = nullptr, *d_rows = nullptr;
@@ -563,6 +564,12 @@ static int init_impl(sr_ctx *c) {
         SR_TRY(dev_alloc(c, &c->d_actions[i], (size_t)c->n_seq0 * o.max_turns));
         SR_TRY(dev_alloc(c, &c->d_logits[i], (size_t)c->n_seq0 * s.vocab));
         SR_TRY(launch_fill_i32(c->d_actions[i], (size_t)c->n_seq0 * o.max_turns, -1, nullptr));
+        SR_TRY(dev_alloc(c, &c->d_orig[i], (size_t)c->n_seq0));
+    }
+    {
+        std::vector<int32_t> ids(c->n_seq0);
+        for (int i = 0; i < c->n_seq0; ++i) ids[i] = i;
+        SR_HIP(hipMemcpy(c->d_orig[0], ids.data(), ids.size() * 4, hipMemcpyHostToDevice));
     }
     SR_TRY(dev_alloc(c, &c->d_greedy, (size_t)c->n_seq0));
     SR_TRY(dev_alloc(c, &c->d_chosen, (size_t)c->n_seq0));
@@ -604,7 +611,8 @@ int sr_init(sr_ctx **out, const sr_model_shape *shape, int n_groups, int G, doub
         s.n_q_heads % s.n_kv_heads || s.n_q_heads / s.n_kv_heads > 16 || !(s.rms_eps > 0.f) || !(s.rope_theta > 0.f))
         return SR_E_ARG;
     if ((opt->page_tokens != 32 && opt->page_tokens != 64 && opt->page_tokens != 128) || opt->max_seq_len < 1 ||
-        opt->max_turns < 1 || opt->max_turns > 32 || opt->action_mod < 0 || opt->max_prefill_rows < 0)
+        opt->max_turns < 1 || opt->max_turns > 32 || opt->action_mod < 0 || opt->max_prefill_rows < 0 ||
+        !(opt->temperature >= 0.f))
         return SR_E_ARG;
     sr_ctx *c = new sr_ctx();
     c->s = s;
@@ -725,7 +733,9 @@ int sr_decode_step(sr_ctx *c, const int32_t *forced, int32_t *out_tokens, void *
     SR_TRY(timed(c, SR_KC_ARGMAX, st, [&] {
         return launch_argmax(c->d_logits[c->cur], n, c->s.vocab, forced, c->d_greedy, c->d_chosen,
                              record ? c->d_actions[c->cur] : nullptr, c->o.max_turns, c->turn - 1,
-                             c->o.action_mod > 0 ? c->o.action_mod : 1, st);
+                             c->o.action_mod > 0 ? c->o.action_mod : 1,
+                             c->o.temperature > 0.f ? 1.0f / c->o.temperature : 0.f, c->o.sample_seed,
+                             c->d_orig[c->cur], c->seq_len, st);
     }));
     if (out_tokens) SR_HIP(hipMemcpyAsync(out_tokens, c->d_greedy, (size_t)n * 4, hipMemcpyDeviceToDevice, st));
     if (c->first_decode_of_turn && c->turn >= 1) {
@@ -809,6 +819,7 @@ int sr_retire_and_compact(sr_ctx *c, int *host_n_live_groups, void *stream) {
             SR_TRY(launch_gather_rows(c->d_actions[nxt], c->d_actions[c->cur], c->d_rows, n,
                                       (size_t)c->o.max_turns * 4, st));
             SR_TRY(launch_gather_rows(c->d_logits[nxt], c->d_logits[c->cur], c->d_rows, n, (size_t)c->s.vocab * 4, st));
+            SR_TRY(launch_gather_rows(c->d_orig[nxt], c->d_orig[c->cur], c->d_rows, n, 4, st));
             c->cur = nxt;
             SR_HIP(hipStreamSynchronize(st));     // h_rows may be rewritten by the next compaction
         }

@@ -151,9 +151,11 @@ int launch_qkv_post(const QkvPostArgs &a, hipStream_t stream);
 
 // greedy[r] = lowest index of the largest logit of row r; tok = forced ? forced[r] : greedy[r];
 // chosen[r] = tok; if actions != null: actions[r*max_turns + turn_idx] = tok % action_mod.
+// inv_temperature > 0: sample instead (Gumbel-max over logits * inv_temperature, uniforms keyed by
+// (seed, orig_seq[r], pos)).
 int launch_argmax(const float *logits, int rows, int vocab, const int32_t *forced, int32_t *greedy_out,
                   int32_t *chosen, int32_t *actions, int max_turns, int turn_idx, int action_mod,
-                  hipStream_t stream);
+                  float inv_temperature, uint64_t seed, const int32_t *orig_seq, int pos, hipStream_t stream);
 
 // ---------------------------------------------------------------------------------------------
 // attention

@@ -348,3 +348,68 @@ def test_batch_larger_than_one_row_block():
     rec, stats, worst, mism, near = run_and_compare(shape, cfg, seed=22, page_tokens=32)
     assert worst <= LOGIT_TOL and mism == 0
     assert stats["n_live_seq"] == 8 * len(rec["final_live_groups"]) < 128
+
+
+def test_temperature_sampling_matches_checker():
+    """T = 0.7 (the paper's rollout temperature): every observation is shared by all members, so the
+    members of a group diverge only through sampling.  (1) On the GPU's own logits the sampled token
+    equals the checker's draw for the same (seed, original sequence id, position) except at near-ties
+    of the perturbed scores; (2) the whole sampled, gated episode matches the checker teacher-forced."""
+    shape = synth.TINY
+    w = synth.make_weights(shape, seed=0)
+    T, sseed = 0.7, 4242
+    cfg = synth.EpisodeConfig("sample", 4, 8, 64, 4, 16, 4, 16, (3,), 0.3, 1.0)   # all groups: shared observations
+    conv = synth.converging_groups(cfg, 1)
+    assert conv.all()
+    prompts = synth.prompts(cfg, shape.vocab, 1)
+    obs_fn = lambda t: synth.observations(cfg, shape.vocab, 1, t, conv)
+    rec = oracle.run_episode(oracle.Model(w), prompts, obs_fn, cfg.G, cfg.turns, cfg.act_len, cfg.action_mod,
+                             cfg.gate_turns, cfg.threshold, keep_logits=True, temperature=T, sample_seed=sseed)
+    # sampling makes members differ: no group is identical at the gate
+    assert all(s > 0 for s in rec["gate"][3]["sums"].values())
+
+    max_len = cfg.prompt_len + cfg.turns * (cfg.obs_len + cfg.act_len)
+    ctx = sr.Context(shape, cfg.n_groups, cfg.G, cfg.threshold, page_tokens=32, max_seq_len=max_len,
+                     max_turns=cfg.turns, action_mod=cfg.action_mod, kv_pool_bytes=1 << 28, temperature=T,
+                     sample_seed=sseed)
+    load_host_weights(ctx, w)
+    ctx.sr_prefill_chunk(dev(prompts), True)
+    worst, own_mism, ep_mism = 0.0, 0, 0
+    pos = cfg.prompt_len
+    for turn in range(cfg.turns):
+        live = rec["live_groups"][turn]
+        rows = [g * cfg.G + m for g in live for m in range(cfg.G)]
+        assert list(ctx.sr_get_live_map()) == rows
+        ctx.sr_prefill_chunk(dev(obs_fn(turn)[rows]), False)
+        pos += cfg.obs_len
+        logits = torch.empty((len(rows), shape.vocab), dtype=torch.float32, device="cuda")
+        drawn = torch.empty(len(rows), dtype=torch.int32, device="cuda")
+        for a in range(cfg.act_len):
+            ctx.sr_get_logits(logits)
+            torch.cuda.synchronize()
+            got = logits.cpu().numpy()
+            ref = np.stack([rec["logits"][turn][a][r] for r in rows])
+            worst = max(worst, float(np.abs(got - ref).max()))
+            forced = rec["tokens"][turn][a, rows]
+            ctx.sr_decode_step(dev(forced), drawn)
+            torch.cuda.synchronize()
+            d = drawn.cpu().numpy()
+            for i, r in enumerate(rows):
+                tok, gap = oracle.sample(got[i].astype(np.float64), T, sseed, r, pos)   # same logits: same draw
+                if d[i] != tok and gap >= 1e-4:
+                    own_mism += 1
+                if d[i] != forced[i] and rec["gaps"][turn][a, r] >= 2 * LOGIT_TOL / T:
+                    ep_mism += 1
+            pos += 1
+        if turn + 1 in cfg.gate_turns:
+            sums = torch.empty(len(live), dtype=torch.int32, device="cuda")
+            ret = torch.empty(len(live), dtype=torch.uint8, device="cuda")
+            ctx.sr_gate(turn + 1, sums, ret)
+            ctx.sr_retire_and_compact()
+            gate = rec["gate"][turn + 1]
+            assert list(sums.cpu().numpy()) == [gate["sums"][g] for g in live]
+            assert list(ret.cpu().numpy().astype(bool)) == [gate["cut"][g] for g in live]
+    ctx.close()
+    print(f"sampling: worst |dlogit| = {worst:.3e}, draw mismatches on own logits = {own_mism}, "
+          f"episode mismatches = {ep_mism}")
+    assert worst <= LOGIT_TOL and own_mism == 0 and ep_mism == 0

@@ -170,3 +170,25 @@ def test_bf16_contract_mode_is_off_by_default_and_small(small):
     assert np.array_equal(exact, again)
     d = np.abs(rounded - exact).max()
     assert 0 < d < 0.05 * np.abs(exact).max()
+
+
+def test_sampler_draws_from_softmax():
+    """Gumbel-max sampling with counter-based uniforms: empirical frequencies over many (sequence,
+    position) keys match softmax(logits / T); draws are reproducible and keyed, not positional."""
+    logits = np.array([1.0, 0.2, -0.5, 2.1, 0.0, 1.4])
+    T = 0.7
+    p = np.exp(logits / T) / np.exp(logits / T).sum()
+    n = 40000
+    counts = np.zeros(6)
+    for i in range(n):
+        tok, gap = oracle.sample(logits, T, 12345, i // 200, i % 200)
+        counts[tok] += 1
+        assert gap >= 0
+    sigma = np.sqrt(n * p * (1 - p))
+    assert np.all(np.abs(counts - n * p) < 4.5 * sigma), (counts / n, p)
+    assert oracle.sample(logits, T, 1, 3, 7) == oracle.sample(logits, T, 1, 3, 7)
+    draws = {oracle.sample(logits, T, 1, s, 7)[0] for s in range(50)}
+    assert len(draws) > 2                                  # the sequence id matters
+    assert oracle.sample(logits, 1e-3, 5, 0, 0)[0] == 3     # T -> 0 recovers the greedy choice
+    flat = [oracle.sample(np.zeros(4), 1.0, 9, s, 0)[0] for s in range(4000)]
+    assert np.all(np.abs(np.bincount(flat, minlength=4) - 1000) < 150)
