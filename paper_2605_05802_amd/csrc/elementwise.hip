@@ -7,27 +7,27 @@
 namespace sr {
 namespace {
 
-// deterministic block-wide sum over 256 threads
-__device__ __forceinline__ float block_sum_256(float v, float *s_red) {
+// deterministic block-wide sum over 512 threads
+__device__ __forceinline__ float block_sum_512(float v, float *s_red) {
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
     const int wave = threadIdx.x >> 6;
     if ((threadIdx.x & 63) == 0) s_red[wave] = v;
     __syncthreads();
-    const float total = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
+    const float total = ((s_red[0] + s_red[1]) + (s_red[2] + s_red[3])) + ((s_red[4] + s_red[5]) + (s_red[6] + s_red[7]));
     __syncthreads();
     return total;
 }
 
 // x = resid (+ partials) or embedding row; resid <- x (if write_resid); out <- bf16(x * rsqrt(mean(x^2)+eps) * gain)
-// H <= 8192: each thread keeps its (at most 4 x 8) values in registers between the two passes.
-__global__ __launch_bounds__(256) void resid_norm_kernel(NormArgs a) {
-    __shared__ float s_red[4];
+// H <= 8192: each thread keeps its (at most 2 x 8) values in registers between the two passes.
+__global__ __launch_bounds__(512) void resid_norm_kernel(NormArgs a) {
+    __shared__ float s_red[8];
     const int m = blockIdx.x;
     const size_t row = (size_t)(m / a.src_dup) * a.src_stride + a.src_off;
     float *x = a.resid + row * a.H;
     const int nvec = a.H >> 3;                       // groups of 8 consecutive features
-    float xv[4][8];
+    float xv[2][8];
     float ss = 0.f;
 
     const uint16_t *e = nullptr;
@@ -36,8 +36,8 @@ __global__ __launch_bounds__(256) void resid_norm_kernel(NormArgs a) {
         e = a.embed + (size_t)tok * a.H;
     }
 #pragma unroll
-    for (int it = 0; it < 4; ++it) {
-        const int v = threadIdx.x + it * 256;
+    for (int it = 0; it < 2; ++it) {
+        const int v = threadIdx.x + it * 512;
         if (v < nvec) {
             float *f = xv[it];
             if (e) {
@@ -79,12 +79,12 @@ __global__ __launch_bounds__(256) void resid_norm_kernel(NormArgs a) {
             }
         }
     }
-    const float total = block_sum_256(ss, s_red);
+    const float total = block_sum_512(ss, s_red);
     const float inv = 1.0f / sqrtf(total / (float)a.H + a.eps);
 
 #pragma unroll
-    for (int it = 0; it < 4; ++it) {
-        const int v = threadIdx.x + it * 256;
+    for (int it = 0; it < 2; ++it) {
+        const int v = threadIdx.x + it * 512;
         if (v < nvec) {
             const float *f = xv[it];
             const uint4 graw = *(const uint4 *)(a.gain + v * 8);
@@ -256,7 +256,7 @@ __global__ void copy_page_kernel(uint4 *kpool, uint4 *vpool, size_t layer_vec, s
 int launch_resid_norm(const NormArgs &a, hipStream_t stream) {
     if (a.rows_out <= 0) return SR_OK;
     if (a.H % 8 || a.H > 8192) return SR_E_ARG;
-    resid_norm_kernel<<<dim3(a.rows_out), dim3(256), 0, stream>>>(a);
+    resid_norm_kernel<<<dim3(a.rows_out), dim3(512), 0, stream>>>(a);
     SR_HIP(hipGetLastError());
     return SR_OK;
 }
