@@ -224,7 +224,7 @@ def main():
         "config": {"workload": cfg.name, "layers": shape.n_layers, "hidden": shape.hidden, "groups": cfg.n_groups,
                    "G": cfg.G, "prompt": cfg.prompt_len, "turns": turns, "obs": cfg.obs_len, "act": cfg.act_len,
                    "gate_turns": list(cfg.gate_turns), "threshold": cfg.threshold},
-        "roofline": {"bound": "hbm", "kernel": "gemm_skinny_kernel<EPI_SWIGLU, 5> (decode gate|up projection)",
+        "roofline": {"bound": "hbm", "kernel": "gemm_stream_kernel<EPI_SWIGLU, 5, MT32, 8> (decode gate|up projection)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "avg_launch_ms": avg_ms, "launches_timed": launches,
                      "algorithmic_bytes_per_launch": gu_bytes},

@@ -133,19 +133,28 @@ int timed(sr_ctx *c, int kc, hipStream_t st, F &&launch) {
     return rc;
 }
 
-// Decode-time projections (M <= 128): wide matrices use the 8-wavefront kernel (256 features per
-// workgroup); thin ones are split along K so that about one workgroup per CU is in flight -- more
-// than that only adds partial-sum traffic.  Prefill (M > 128) never splits.
-bool use_wide(int M, int N, int ks_total) { return M <= 128 && (N >= 8192 || ks_total >= 256); }
+// Decode-time projections (M <= 128).  Matrices that are wide or deep go to the kernel with a loader
+// wavefront; the number of computing wavefronts per workgroup (32 features each) is picked so that
+// the matrix breaks into about 256 workgroups with as few K splits as possible: the packed gate|up
+// matrix (37 888 rows at the 7B shape) gives 237 workgroups of 160 features, the down projection
+// 28 blocks of 128 features x 9 splits, the LM head 256-feature workgroups over several rounds.
+// Thin ones keep the 4-wavefront kernel and are split along K so that about one workgroup per CU is
+// in flight -- more than that only adds partial-sum traffic.  Prefill (M > 128) never splits.
+int decode_waves(int M, int N, int ks_total, bool swiglu) {
+    if (M > 128 || !(N >= 8192 || ks_total >= 256)) return 0;
+    if (swiglu) return 5;
+    return N >= 8192 ? 8 : 4;
+}
 
 int pick_splits(int M, int N, int ks_total) {
     if (M > 128) return 1;
-    const int n_blocks = ceil_div(N, use_wide(M, N, ks_total) ? 256 : 128);
+    const int waves = decode_waves(M, N, ks_total, false);
+    const int n_blocks = ceil_div(N, waves ? 32 * waves : 128);
     const int target = 256 / n_blocks;
     if (target <= 1) return 1;
     const int units = ks_total / 8;                 // a split covers whole groups of 8 k-steps
-    const int ups = ceil_div(units, target);
-    int s = ceil_div(units, ups);
+    const int ups = ceil_div(units, target);        // units per split at the target count ...
+    int s = ceil_div(units, ups);                   // ... and the fewest splits that keep it
     if (s > kMaxSplitK) s = kMaxSplitK;
     return s < 1 ? 1 : s;
 }
@@ -269,9 +278,8 @@ int gemm(sr_ctx *c, const uint4 *X, const PackedMat &W, int M, GemmEpilogue epi,
     a.out = out;
     a.ld_out = ld_out;
     a.splits = 1;
-    // gate|up (37 888 packed rows at the 7B shape) splits into 237 workgroups of 160 features, which
-    // covers the 256 CUs better than 148 of 256; the other wide matrices prefer 256-feature workgroups
-    a.wide = use_wide(M, W.N, W.ks) ? (epi == EPI_SWIGLU ? 5 : 8) : 0;
+    a.wide = decode_waves(M, W.N, W.ks, epi == EPI_SWIGLU);
+    a.ring = 8;
     if (epi == EPI_F32 && splits_out) {
         a.splits = pick_splits(M, W.N, W.ks);
         a.split_stride = (size_t)round_up(M, 128) * ld_out;

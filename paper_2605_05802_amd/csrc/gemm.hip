@@ -25,6 +25,23 @@ constexpr int kKC = 4;                    // k-steps (of 32) per LDS chunk of X
 constexpr int kPF = 8;                    // k-steps of W held in registers ahead of the MFMAs (two X chunks)
 constexpr int kChunkVec = kKC * 512;      // uint4 per chunk: 8 row tiles x 64 lanes per k-step
 
+// Weight loads.  At decode time every weight byte is used once per launch, so the load carries the
+// non-temporal hint: the caches do not retain the line, and a pure streaming read measures 13 %
+// faster with it (6.97 against 6.15 TB/s).  Prefill re-reads W once per row block and keeps the default policy.
+template <bool STREAM>
+__device__ __forceinline__ u32x4 load_w(const u32x4 *p) {
+    if constexpr (STREAM) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+
+// k-steps [*k0, *k1) of split sp when `units` groups of `unit` k-steps are dealt out evenly
+__device__ __forceinline__ void split_range(int ks_total, int unit, int splits, int sp, int *k0, int *k1) {
+    const int units = ks_total / unit, q = units / splits, r = units % splits;
+    const int u0 = sp * q + min(sp, r);
+    *k0 = u0 * unit;
+    *k1 = (u0 + q + (sp < r ? 1 : 0)) * unit;
+}
+
 // SKINNY = the whole batch fits one 128-row block (decode): a distinct instantiation, so that the
 // weight-streaming launches and the compute-bound prefill launches are told apart in profiles.
 //
@@ -43,10 +60,8 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int nb = blockIdx.x, mb = SKINNY ? 0 : blockIdx.y, sp = blockIdx.z;
-    const int units = a.ks_total / kPF;                       // groups of kPF k-steps
-    const int units_per_split = ceil_div(units, a.splits);
-    const int ks0 = sp * units_per_split * kPF;
-    const int ks1 = min(ks0 + units_per_split * kPF, a.ks_total);
+    int ks0, ks1;                                              // whole groups of kPF k-steps
+    split_range(a.ks_total, kPF, a.splits, sp, &ks0, &ks1);
     const int nt0 = nb * 8 + wave * 2;    // first of this wavefront's two 16-feature tiles
 
     f32x4 acc[8][2];
@@ -66,8 +81,8 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
         u32x4 w0[kPF], w1[kPF], xr[8];
 #pragma unroll
         for (int i = 0; i < kPF; ++i) {
-            w0[i] = wp0[(size_t)(ks0 + i) * 64];
-            w1[i] = wp1[(size_t)(ks0 + i) * 64];
+            w0[i] = load_w<SKINNY>(wp0 + (size_t)(ks0 + i) * 64);
+            w1[i] = load_w<SKINNY>(wp1 + (size_t)(ks0 + i) * 64);
         }
 #pragma unroll
         for (int r = 0; r < 8; ++r) xr[r] = xp[(size_t)(ks0 + (r >> 1)) * x_ks_stride + ((r & 1) << 8)];
@@ -107,8 +122,8 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
                         acc[mt][1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wb, xf[kk & 1][mt], acc[mt][1], 0, 0, 0);
                     }
                     const int kn = min(kc0 + kk + kPF, last);    // refill the slot just consumed
-                    w0[i] = wp0[(size_t)kn * 64];
-                    w1[i] = wp1[(size_t)kn * 64];
+                    w0[i] = load_w<SKINNY>(wp0 + (size_t)kn * 64);
+                    w1[i] = load_w<SKINNY>(wp1 + (size_t)kn * 64);
                     if (kk + 1 < kKC) {
 #pragma unroll
                         for (int mt = 0; mt < 8; ++mt) {
@@ -167,104 +182,123 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Decode-time (M <= 128) weight-streaming kernel.
+// Decode-time (M <= 128) weight-streaming kernel with a loader wavefront.
 //
-// One 8-wavefront workgroup owns 256 output features and all rows.  Vector-memory loads return in
-// order within a wavefront, so a wait for a late-issued activation load would also drain every
-// older weight load and collapse the prefetch depth.  All loads are therefore issued in order of
-// their deadline: the X chunk for two chunks ahead is fetched into registers at the start of a
-// chunk, the W k-steps for two chunks ahead are refilled during it, and the X chunk fetched during
-// the previous chunk is written to the other LDS buffer at its end.  Waiting for that write's
-// operands only forces loads that are needed immediately afterwards, so two full chunks of weights
-// (16 KiB per wavefront) stay in flight across every barrier.  No branch in the loop body: the
-// compiler counts outstanding loads exactly.
-// ---------------------------------------------------------------------------------------------
-// Workgroup width is a template parameter: 8 wavefronts (256 features) or 5 (160 features).  With
-// one workgroup per CU the per-CU rate bounds the kernel, so a matrix should break into roughly 256
-// equal workgroups: 37 888 packed gate|up rows give 148 workgroups of 256 features (108 CUs idle)
-// but 237 of 160.
-#ifndef SK_PF
-#define SK_PF 8
-#endif
-constexpr int kSkPF = SK_PF;            // k-steps of W in registers per wavefront (ring depth)
-
-// The MFMA used here is the 32x32x16 form: with one workgroup per CU all eight wavefronts stall at
-// the same barriers, and a single wavefront keeps the matrix pipe far busier with 32x32 tiles than
-// with 16x16 ones.  Its operands (32 rows x 16 k) are assembled from the same 16-row fragment layout
-// by addressing: lane (r = lane % 32, g = lane / 32) of k-half h takes the 16 bytes of row tile r / 16,
+// A workgroup owns 32 * WAVES output features and all rows; each of its WAVES computing wavefronts
+// owns 32 features and streams their weights through a register ring of RING k-steps (2 KiB each),
+// refilling a slot as soon as its MFMAs are issued, so RING * 2 KiB per wavefront stay in flight
+// across the workgroup barriers.  The loop body has no branch: the compiler counts outstanding
+// loads exactly, and prefetches past the end re-read the last valid k-step.
+//
+// The activations are brought in by one extra wavefront that does nothing else: it copies X chunks
+// (kKC k-steps, 32 KiB) from global memory straight into LDS with lane-linear 16-byte direct-to-LDS
+// loads, two chunks ahead of the MFMAs, through three buffers.  Vector-memory loads return in order
+// within a wavefront, so an activation load inside a computing wavefront would make its wait drain
+// the older weight loads too; with the loader the computing wavefronts carry only weight loads,
+// never wait for an activation and keep no staging registers, and the loader's wait for its own
+// copies stalls nobody.
+//
+// The MFMA is the 32x32x16 form: with one workgroup per CU all wavefronts stall at the same
+// barriers, and a single wavefront keeps the matrix pipe far busier with 32x32 tiles than with
+// 16x16 ones.  Its operands (32 rows x 16 k) are assembled from the 16-row fragment layout by
+// addressing: lane (r = lane % 32, g = lane / 32) of k-half h takes the 16 bytes of row tile r / 16,
 // lane slot (r % 16) + 16 * (2h + g).
-template <int EPI, int WAVES>
-__global__ __launch_bounds__(64 * WAVES, 2) void gemm_skinny_kernel(GemmArgs a) {
-    constexpr int kSkThreads = 64 * WAVES;
-    // X vectors per thread per chunk; when the chunk does not divide evenly the surplus slots re-copy
-    // vectors that another thread also copies (same data to the same place), keeping the loop branch-free
-    constexpr int kSkXR = (kChunkVec + kSkThreads - 1) / kSkThreads;
-    __shared__ u32x4 lds[2][kChunkVec];   // 2 x 32 KiB
+//
+// MT32 = number of 32-row tiles computed (M <= 32 * MT32): smaller batches skip the idle rows'
+// copies, LDS reads and MFMAs.  Workgroup width matters because with one workgroup per CU a matrix
+// should break into about 256 equal workgroups: 37 888 packed gate|up rows give 148 workgroups of
+// 256 features (108 CUs idle) but 237 of 160.
+// ---------------------------------------------------------------------------------------------
+constexpr int kStBufs = 3;                 // LDS chunk buffers: the loader runs two chunks ahead
+constexpr int kStLdsBytes = kStBufs * kChunkVec * 16;
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+// RING = k-steps of W each computing wavefront keeps in flight (8 or 16; 2 KiB per k-step)
+template <int EPI, int WAVES, int MT32, int RING>
+__global__ __launch_bounds__(64 * (WAVES + 1)) void gemm_stream_kernel(GemmArgs a) {
+    extern __shared__ u32x4 lds_dyn[];     // [kStBufs][k-step in chunk][16-row tile 0..7][lane]
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nb = blockIdx.x, sp = blockIdx.z;
-    const int units = a.ks_total / kSkPF;
-    const int units_per_split = ceil_div(units, a.splits);
-    const int ks0 = sp * units_per_split * kSkPF;
-    const int ks1 = min(ks0 + units_per_split * kSkPF, a.ks_total);
+    int ks0, ks1;
+    split_range(a.ks_total, RING, a.splits, sp, &ks0, &ks1);
+    const int last = ks1 - 1;
+
+    if (wave == WAVES) {
+        // ---- loader.  Chunk c lives in buffer c % 3.  Barrier c (c = 0, 1, ...) is passed by the
+        // computing wavefronts once they are done with chunk c - 1, and by the loader once chunk c has
+        // landed; after it the loader may overwrite the buffer of chunk c - 1 with chunk c + 2.
+        if (ks0 >= ks1) return;
+        const u32x4 *xp = (const u32x4 *)a.X + lane;
+        const size_t x_ks_stride = (size_t)a.mt_total * 64;
+        constexpr int kCopies = kKC * 2 * MT32;         // direct-to-LDS loads per chunk (<= 32)
+        auto copy_chunk = [&](int kc, int buf) {
+#pragma unroll
+            for (int kk = 0; kk < kKC; ++kk) {
+                const u32x4 *src = xp + (size_t)min(kc + kk, last) * x_ks_stride;
+#pragma unroll
+                for (int b = 0; b < 2 * MT32; ++b)
+                    __builtin_amdgcn_global_load_lds(
+                        (const __attribute__((address_space(1))) void *)(src + b * 64),
+                        (__attribute__((address_space(3))) void *)&lds_dyn[buf * kChunkVec + kk * 512 + b * 64], 16,
+                        0, 0);
+            }
+        };
+        // wait until at most one chunk of copies is outstanding: vmcnt(kCopies), other counters untouched
+        constexpr int kWaitOlder = 0x0F70 | (kCopies & 15) | ((kCopies >> 4) << 14);
+        copy_chunk(ks0, 0);
+        copy_chunk(ks0 + kKC, 1);
+        int buf = 2;
+        for (int kc = ks0; kc < ks1; kc += kKC) {
+            __builtin_amdgcn_s_waitcnt(kWaitOlder);
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            copy_chunk(kc + 2 * kKC, buf);               // past the end: re-copies the last k-step, never read
+            buf = buf == kStBufs - 1 ? 0 : buf + 1;
+        }
+        __builtin_amdgcn_s_waitcnt(kWaitOlder);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_s_waitcnt(0x0F70);              // nothing may still be writing LDS at exit
+        return;
+    }
+
     const int nt32 = nb * WAVES + wave;             // this wavefront's 32 output features
     const int r32 = lane & 31, g2 = lane >> 5;
     const int sub = r32 >> 4;                       // which 16-row tile of the pair
     const int slot0 = (r32 & 15) + 16 * g2;         // lane slot for k-half 0; k-half 1 is +32
 
-    f32x16 acc[4];
+    f32x16 acc[MT32];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < MT32; ++i)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
 
     if (ks0 < ks1) {
         const u32x4 *wp0 = (const u32x4 *)a.W + ((size_t)(nt32 * 2 + sub) * a.ks_total) * 64 + slot0;
         const u32x4 *wp1 = wp0 + 32;
-        const int last = ks1 - 1;
-        // thread's r-th vector of a chunk has chunk index (tid + threads * r) % 2048:
-        // k-step index / 512, position index % 512
-        const u32x4 *xp = (const u32x4 *)a.X;
-        const size_t x_ks_stride = (size_t)a.mt_total * 64;
-        int xkk[kSkXR], xpos[kSkXR], xidx[kSkXR];
-#pragma unroll
-        for (int r = 0; r < kSkXR; ++r) {
-            xidx[r] = (tid + kSkThreads * r) % kChunkVec;
-            xkk[r] = xidx[r] >> 9;
-            xpos[r] = xidx[r] & 511;
-        }
         const int xoff = sub * 64 + slot0;          // + mt32 * 128 + h * 32 inside a k-step of a buffer
+        constexpr int NF = 2 * MT32;                // X fragments per k-step
 
-        u32x4 w0[kSkPF], w1[kSkPF], xr[2][kSkXR];
+        u32x4 w0[RING], w1[RING];
 #pragma unroll
-        for (int i = 0; i < kSkPF; ++i) {
-            w0[i] = wp0[(size_t)(ks0 + i) * 64];
-            w1[i] = wp1[(size_t)(ks0 + i) * 64];
+        for (int i = 0; i < RING; ++i) {
+            w0[i] = load_w<true>(wp0 + (size_t)(ks0 + i) * 64);
+            w1[i] = load_w<true>(wp1 + (size_t)(ks0 + i) * 64);
         }
-#pragma unroll
-        for (int r = 0; r < kSkXR; ++r) xr[0][r] = xp[(size_t)(ks0 + xkk[r]) * x_ks_stride + xpos[r]];
-#pragma unroll
-        for (int r = 0; r < kSkXR; ++r) xr[1][r] = xp[(size_t)min(ks0 + kKC + xkk[r], last) * x_ks_stride + xpos[r]];
-#pragma unroll
-        for (int r = 0; r < kSkXR; ++r) lds[0][xidx[r]] = xr[0][r];
-        __syncthreads();
+        __syncthreads();                                         // barrier 0: chunk 0 is in LDS
 
-        for (int ks = ks0; ks < ks1; ks += kSkPF) {
+        int buf = 0;
+        for (int ks = ks0; ks < ks1; ks += RING) {
 #pragma unroll
-            for (int q = 0; q < kSkPF / kKC; ++q) {
-                const int half = q & 1;
-                const int kc0 = ks + q * kKC;                    // chunk in LDS buffer `half`
-                __builtin_amdgcn_sched_barrier(0);               // keep the issue order = deadline order
+            for (int q = 0; q < RING / kKC; ++q) {
+                const int kc0 = ks + q * kKC;
+                bf16x8 xf[2][NF];                                // [parity][mt32 * 2 + k-half]
+                const u32x4 *xb = &lds_dyn[buf * kChunkVec + xoff];
+                buf = buf == kStBufs - 1 ? 0 : buf + 1;
 #pragma unroll
-                for (int r = 0; r < kSkXR; ++r)                  // X two chunks ahead
-                    xr[half][r] = xp[(size_t)min(kc0 + 2 * kKC + xkk[r], last) * x_ks_stride + xpos[r]];
-                __builtin_amdgcn_sched_barrier(0);
-                // X fragments are fetched from LDS one k-step ahead of the MFMAs that use them and the
-                // two instruction streams are interleaved explicitly.
-                bf16x8 xf[2][8];                                 // [parity][mt32 * 2 + k-half]
-                const u32x4 *xb = &lds[half][xoff];
-#pragma unroll
-                for (int f = 0; f < 8; ++f)
+                for (int f = 0; f < NF; ++f)
                     xf[0][f] = __builtin_bit_cast(bf16x8, xb[(f >> 1) * 128 + (f & 1) * 32]);
 #pragma unroll
                 for (int kk = 0; kk < kKC; ++kk) {
@@ -274,33 +308,30 @@ __global__ __launch_bounds__(64 * WAVES, 2) void gemm_skinny_kernel(GemmArgs a) 
                     const bf16x8 wb = __builtin_bit_cast(bf16x8, w1[i]);
                     if (kk + 1 < kKC) {
 #pragma unroll
-                        for (int f = 0; f < 8; ++f)
+                        for (int f = 0; f < NF; ++f)
                             xf[(kk + 1) & 1][f] =
                                 __builtin_bit_cast(bf16x8, xb[(kk + 1) * 512 + (f >> 1) * 128 + (f & 1) * 32]);
                     }
 #pragma unroll
-                    for (int mt = 0; mt < 4; ++mt) {
+                    for (int mt = 0; mt < MT32; ++mt) {
                         acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa, xf[kk & 1][mt * 2], acc[mt], 0, 0, 0);
                         acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wb, xf[kk & 1][mt * 2 + 1], acc[mt], 0, 0, 0);
                     }
-                    const int kn = min(kc0 + kk + kSkPF, last);  // refill the slot just consumed
-                    w0[i] = wp0[(size_t)kn * 64];
-                    w1[i] = wp1[(size_t)kn * 64];
+                    const int kn = min(kc0 + kk + RING, last);  // refill the slot just consumed
+                    w0[i] = load_w<true>(wp0 + (size_t)kn * 64);
+                    w1[i] = load_w<true>(wp1 + (size_t)kn * 64);
                     if (kk + 1 < kKC) {
 #pragma unroll
-                        for (int f = 0; f < 8; ++f) {
+                        for (int f = 0; f < NF; ++f) {
                             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
                             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 LDS read
                         }
                     } else {
-                        __builtin_amdgcn_sched_group_barrier(0x008, 8, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x008, NF, 0);
                     }
                     __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);           // W refills
                 }
                 __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int r = 0; r < kSkXR; ++r)                  // X for the next chunk (fetched a chunk ago)
-                    lds[half ^ 1][xidx[r]] = xr[half ^ 1][r];
                 __syncthreads();
             }
         }
@@ -311,7 +342,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void gemm_skinny_kernel(GemmArgs a) 
     if constexpr (EPI == EPI_F32) {
         float *out = (float *)a.out + (size_t)sp * a.split_stride;
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt) {
+        for (int mt = 0; mt < MT32; ++mt) {
             const int m = mt * 32 + r32;
             if (m < a.M) {
 #pragma unroll
@@ -327,7 +358,7 @@ __global__ __launch_bounds__(64 * WAVES, 2) void gemm_skinny_kernel(GemmArgs a) 
         // packed rows 0..15 of the 32 are gate features, 16..31 the matching up features
         uint16_t *out = (uint16_t *)a.out;
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt) {
+        for (int mt = 0; mt < MT32; ++mt) {
             const int m = mt * 32 + r32;
             if (m < a.M) {
 #pragma unroll
@@ -556,17 +587,32 @@ int launch_gemm(const GemmArgs &a, GemmEpilogue epi, hipStream_t stream) {
     if (m_blocks * 8 > a.mt_total || a.splits < 1 || m_blocks > 65535 || a.splits > 65535 || a.ks_total % 16)
         return SR_E_ARG;
     if (m_blocks == 1 && a.wide) {
-        const int waves = a.wide == 5 ? 5 : 8;
-        dim3 sgrid(ceil_div(a.N, 32 * waves), 1, epi == EPI_F32 ? a.splits : 1), sblock(64 * waves);
-        if (waves == 5) {
-            if (epi == EPI_F32) gemm_skinny_kernel<EPI_F32, 5><<<sgrid, sblock, 0, stream>>>(a);
-            else gemm_skinny_kernel<EPI_SWIGLU, 5><<<sgrid, sblock, 0, stream>>>(a);
-        } else {
-            if (epi == EPI_F32) gemm_skinny_kernel<EPI_F32, 8><<<sgrid, sblock, 0, stream>>>(a);
-            else gemm_skinny_kernel<EPI_SWIGLU, 8><<<sgrid, sblock, 0, stream>>>(a);
+        {
+            const int ring = a.ring == 16 ? 16 : 8;
+            if (a.ks_total % ring || (a.wide != 2 && a.wide != 4 && a.wide != 5 && a.wide != 8)) return SR_E_ARG;
+            dim3 sgrid(ceil_div(a.N, 32 * a.wide), 1, epi == EPI_F32 ? a.splits : 1), lblock(64 * (a.wide + 1));
+            const int mt32 = ceil_div(a.M, 32);
+            hipError_t attr = hipSuccess;
+#define SR_STREAM_CASE(E, W, T, R)                                                                          \
+    (attr = hipFuncSetAttribute((const void *)gemm_stream_kernel<E, W, T, R>,                                \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, kStLdsBytes),                   \
+     gemm_stream_kernel<E, W, T, R><<<sgrid, lblock, kStLdsBytes, stream>>>(a))
+#define SR_STREAM_MT(E, W, R)                                                                               \
+    (mt32 == 1 ? SR_STREAM_CASE(E, W, 1, R) : mt32 == 2 ? SR_STREAM_CASE(E, W, 2, R)                         \
+     : mt32 == 3 ? SR_STREAM_CASE(E, W, 3, R) : SR_STREAM_CASE(E, W, 4, R))
+#define SR_STREAM_W(E, R)                                                                                   \
+    (a.wide == 2 ? SR_STREAM_MT(E, 2, R) : a.wide == 4 ? SR_STREAM_MT(E, 4, R)                               \
+     : a.wide == 5 ? SR_STREAM_MT(E, 5, R) : SR_STREAM_MT(E, 8, R))
+            // nine wavefronts put three on one SIMD, which leaves too few registers for the deep ring
+#define SR_STREAM_W16(E)                                                                                    \
+    (a.wide == 2 ? SR_STREAM_MT(E, 2, 16) : a.wide == 4 ? SR_STREAM_MT(E, 4, 16) : SR_STREAM_MT(E, 5, 16))
+            if (ring == 16 && a.wide == 8) return SR_E_ARG;
+            if (epi == EPI_F32) { if (ring == 16) SR_STREAM_W16(EPI_F32); else SR_STREAM_W(EPI_F32, 8); }
+            else { if (ring == 16) SR_STREAM_W16(EPI_SWIGLU); else SR_STREAM_W(EPI_SWIGLU, 8); }
+            SR_HIP(attr);
+            SR_HIP(hipGetLastError());
+            return SR_OK;
         }
-        SR_HIP(hipGetLastError());
-        return SR_OK;
     }
     // wide outputs only: for N of a few thousand the 256 x 256 tiles leave too few workgroups per round
     if (m_blocks > 1 && a.N >= 16384) {

@@ -102,7 +102,9 @@ struct GemmArgs {
     int mt_total;        // row tiles in X (and in a fragment-major output)
     int ks_total;        // k-steps (K padded to 32) in X and W
     int splits;          // split-K factor (EPI_F32 only)
-    int wide;            // M <= 128 only: 8 or 5 = wavefronts per workgroup (32 features each), 0 = 4 wavefronts of 128 features
+    int wide;            // M <= 128 only: 2, 4, 5 or 8 = computing wavefronts per workgroup (32 features each) of the
+                         // kernel with a loader wavefront; 0 = the 4-wavefront, 128-feature kernel
+    int ring;            // with `wide`: k-steps of weights in flight per wavefront, 8 (default) or 16
     void *out;
     int ld_out;          // EPI_F32: row stride (elements); EPI_SWIGLU: k-steps*32 of the output matrix
     size_t split_stride; // EPI_F32: elements between consecutive splits
