@@ -27,7 +27,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // One launch may cover two phases (decode: the shared-prompt phase followed by the private phase), so
 // that the short, narrow shared phase overlaps the private one instead of running alone.
 template <int D, int RT>
-__global__ __launch_bounds__(256) void attn_kernel(AttnArgs a, AttnPhase p0, AttnPhase p1, int n0, int n_items) {
+__global__ __launch_bounds__(256, RT == 1 ? 3 : 2) void attn_kernel(AttnArgs a, AttnPhase p0, AttnPhase p1, int n0, int n_items) {
     constexpr int KS = D / 32;     // k-steps of the QK^T contraction
     constexpr int DT = D / 16;     // 16-wide tiles of the head dimension
     const int lane = threadIdx.x & 63;
@@ -39,8 +39,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a, AttnPhase p0, Att
     const AttnPhase &p = second ? p1 : p0;
     const int item = second ? gitem - n0 : gitem;
 
-    // item -> (unit, kv head, split, q tile): the q tiles of one split are neighbours, so the
-    // wavefronts of a workgroup that share K/V blocks fetch them at the same time
+    // item -> (unit, kv head, split, q tile): the q tiles of one split are neighbours
     int rest = item;
     const int qtile = rest % p.items_per_unit; rest /= p.items_per_unit;
     const int split = rest % p.n_splits; rest /= p.n_splits;
@@ -49,6 +48,15 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a, AttnPhase p0, Att
     const int n_rep = a.n_q / a.n_kv;
 
     const int c = lane & 15, g = lane >> 4;
+    const int32_t *pt = a.page_table + (size_t)unit * p.pt_row_stride * a.pt_stride;
+    const int blocks_per_page = a.page_tokens >> 5;
+    const size_t block_elems = (size_t)32 * D;
+    auto block_base = [&](int t0) -> size_t {
+        const int page = pt[t0 / a.page_tokens];
+        const int blk = (t0 % a.page_tokens) >> 5;
+        return (((size_t)page * a.n_kv + kvh) * blocks_per_page + blk) * block_elems;
+    };
+    const int t_lo = p.t_begin + split * p.split_tokens;
 
     // query rows of this lane's column c in each row tile
     bf16x8 qf[RT][KS];
@@ -76,8 +84,9 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a, AttnPhase p0, Att
     for (int rt = 0; rt < RT; ++rt) max_limit = max(max_limit, limit[rt]);
 #pragma unroll
     for (int off = 1; off < 16; off <<= 1) max_limit = max(max_limit, __shfl_xor(max_limit, off, 64));
-    const int t_lo = p.t_begin + split * p.split_tokens;
-    const int t_hi = min(min(p.t_end, t_lo + p.split_tokens), max_limit + 1);
+    // the same in every lane after the reduction; kept in a scalar register so that the block loop, the
+    // page-table lookups and the block addresses stay on the scalar unit
+    const int t_hi = __builtin_amdgcn_readfirstlane(min(min(p.t_end, t_lo + p.split_tokens), max_limit + 1));
 
     f32x4 o[DT][RT];
 #pragma unroll
@@ -87,74 +96,37 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a, AttnPhase p0, Att
     float mrun[RT], lrun[RT];
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) { mrun[rt] = kNegBig; lrun[rt] = 0.f; }
-
-    const int32_t *pt = a.page_table + (size_t)unit * p.pt_row_stride * a.pt_stride;
-    const int blocks_per_page = a.page_tokens >> 5;
-    const size_t block_elems = (size_t)32 * D;
     const float scale_log2 = a.scale * 1.4426950408889634f;
 
-    // K and V of block i+1 are requested before block i is consumed, so one block's worth of loads
-    // (16 KiB per wavefront at d = 128) is always in flight.
-    bf16x8 kf[2][KS], vf[DT], kn[2][KS], vn[DT];
-    auto block_base = [&](int t0) -> size_t {
-        const int page = pt[t0 / a.page_tokens];
-        const int blk = (t0 % a.page_tokens) >> 5;
-        return (((size_t)page * a.n_kv + kvh) * blocks_per_page + blk) * block_elems;
-    };
-    constexpr bool kPrefetch = (RT == 1);               // two row tiles leave no registers for it
-    if (kPrefetch && t_lo < t_hi) {
-        const size_t base = block_base(t_lo);
-        const uint16_t *kb = a.kpool + base, *vb = a.vpool + base;
+    bf16x8 kf[2][KS], vf[DT];
+    auto load_k = [&](const uint16_t *kb) {
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks)
-                kn[tt][ks] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(kb + ((ks * 32 + tt * 16 + c) * 32 + 8 * g)));
+                kf[tt][ks] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(kb + ((ks * 32 + tt * 16 + c) * 32 + 8 * g)));
+    };
+    auto load_v = [&](const uint16_t *vb) {
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
-            vn[dt] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(vb + ((dt * 16 + c) * 32 + 8 * g)));
-    }
-    for (int t0 = t_lo; t0 < t_hi; t0 += 32) {          // t_lo is a multiple of 32
-        if constexpr (kPrefetch) {
+            vf[dt] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(vb + ((dt * 16 + c) * 32 + 8 * g)));
+    };
+    // S^T = K Q^T for all row tiles
+    auto scores = [&](f32x4 (&s)[RT][2]) {
 #pragma unroll
-            for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) kf[tt][ks] = kn[tt][ks];
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt) vf[dt] = vn[dt];
-        }
-        {
-            const int tn = (kPrefetch && t0 + 32 < t_hi) ? t0 + 32 : t0;   // last block: harmless re-read
-            const size_t base = block_base(tn);
-            const uint16_t *kb = a.kpool + base, *vb = a.vpool + base;
-#pragma unroll
-            for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks)
-                    kn[tt][ks] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(kb + ((ks * 32 + tt * 16 + c) * 32 + 8 * g)));
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-                vn[dt] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(vb + ((dt * 16 + c) * 32 + 8 * g)));
-        }
-        if constexpr (!kPrefetch) {
-#pragma unroll
-            for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) kf[tt][ks] = kn[tt][ks];
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt) vf[dt] = vn[dt];
-        }
-
-#pragma unroll
-        for (int rt = 0; rt < RT; ++rt) {
-            f32x4 s[2];
+        for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
             for (int tt = 0; tt < 2; ++tt) {
-                s[tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+                s[rt][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks)
-                    s[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[tt][ks], qf[rt][ks], s[tt], 0, 0, 0);
+                    s[rt][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[tt][ks], qf[rt][ks], s[rt][tt], 0, 0, 0);
             }
+    };
+    // online softmax of one block; leaves the packed probabilities and the rescale factor per row tile
+    auto softmax = [&](f32x4 (&s)[RT][2], int t0, bf16x8 (&pf)[RT], float (&alpha)[RT]) {
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
             // lane holds tokens t0 + tt*16 + 4g + e of query row (rt, c)
             const int lim = min(limit[rt], t_hi - 1);
             float bmax = kNegBig;
@@ -164,13 +136,13 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a, AttnPhase p0, Att
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     ok[tt][e] = (t0 + tt * 16 + 4 * g + e) <= lim;
-                    s[tt][e] = ok[tt][e] ? s[tt][e] * scale_log2 : kNegBig;
-                    bmax = fmaxf(bmax, s[tt][e]);
+                    s[rt][tt][e] = ok[tt][e] ? s[rt][tt][e] * scale_log2 : kNegBig;
+                    bmax = fmaxf(bmax, s[rt][tt][e]);
                 }
             bmax = fmaxf(bmax, __shfl_xor(bmax, 16, 64));
             bmax = fmaxf(bmax, __shfl_xor(bmax, 32, 64));
             const float mnew = fmaxf(mrun[rt], bmax);
-            const float alpha = exp2f(mrun[rt] - mnew);
+            alpha[rt] = exp2f(mrun[rt] - mnew);
             mrun[rt] = mnew;
             float psum = 0.f;
             float pv[8];
@@ -178,19 +150,69 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a, AttnPhase p0, Att
             for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    const float pe = ok[tt][e] ? exp2f(s[tt][e] - mnew) : 0.f;
+                    const float pe = ok[tt][e] ? exp2f(s[rt][tt][e] - mnew) : 0.f;
                     pv[tt * 4 + e] = pe;
                     psum += pe;
                 }
-            lrun[rt] = lrun[rt] * alpha + psum;
+            lrun[rt] = lrun[rt] * alpha[rt] + psum;
             const uint4 praw = make_uint4(pack_bf16x2(pv[0], pv[1]), pack_bf16x2(pv[2], pv[3]),
                                           pack_bf16x2(pv[4], pv[5]), pack_bf16x2(pv[6], pv[7]));
-            const bf16x8 pf = __builtin_bit_cast(bf16x8, praw);
+            pf[rt] = __builtin_bit_cast(bf16x8, praw);
+        }
+    };
+    // O^T = alpha O^T + V^T P^T
+    auto accumulate = [&](const bf16x8 (&pf)[RT], const float (&alpha)[RT]) {
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt) {
-                o[dt][rt] *= alpha;
-                o[dt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], pf, o[dt][rt], 0, 0, 0);
+                o[dt][rt] *= alpha[rt];
+                o[dt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf[dt], pf[rt], o[dt][rt], 0, 0, 0);
             }
+    };
+
+    if constexpr (RT == 1) {
+        // Software pipeline without spare registers: the K fragments of the next block are requested
+        // into the registers of the current ones as soon as the score MFMAs have consumed them, and
+        // the V fragments likewise after the P.V MFMAs, so 8 KiB per wavefront (d = 128) are in
+        // flight behind the softmax and behind the next block's scores.  The register budget stays
+        // low enough for three wavefronts per SIMD, so every item of a decode step is resident at once.
+        if (t_lo < t_hi) {
+            const size_t base = block_base(t_lo);
+            load_k(a.kpool + base);
+            load_v(a.vpool + base);
+        }
+        for (int t0 = t_lo; t0 < t_hi; t0 += 32) {          // t_lo is a multiple of 32
+            const int tn = t0 + 32 < t_hi ? t0 + 32 : t0;   // after the last block: harmless re-read
+            const size_t base_n = block_base(tn);
+            f32x4 s[RT][2];
+            scores(s);
+            // the scheduling fences keep each refill where it is written: right behind the last use
+            // of the registers it overwrites, a whole softmax (or score pass) ahead of its first use
+            __builtin_amdgcn_sched_barrier(0);
+            load_k(a.kpool + base_n);
+            __builtin_amdgcn_sched_barrier(0);
+            bf16x8 pf[RT];
+            float alpha[RT];
+            softmax(s, t0, pf, alpha);
+            accumulate(pf, alpha);
+            __builtin_amdgcn_sched_barrier(0);
+            load_v(a.vpool + base_n);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    } else {
+        // Two row tiles (prefill): the registers leave no room for a prefetch; K and V of a block are
+        // requested together at the top of its iteration.
+        for (int t0 = t_lo; t0 < t_hi; t0 += 32) {
+            const size_t base = block_base(t0);
+            load_k(a.kpool + base);
+            load_v(a.vpool + base);
+            f32x4 s[RT][2];
+            scores(s);
+            bf16x8 pf[RT];
+            float alpha[RT];
+            softmax(s, t0, pf, alpha);
+            accumulate(pf, alpha);
         }
     }
 
