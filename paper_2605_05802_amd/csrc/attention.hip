@@ -224,6 +224,7 @@ __global__ __launch_bounds__(256, RT == 1 ? 3 : 2) void attn_kernel(AttnArgs a, 
         l += __shfl_xor(l, 32, 64);
         const size_t prow = (size_t)item * (16 * RT) + rt * 16 + c;
         float *po = p.part_o + prow * D;
+        if (limit[rt] < 0) continue;        // padding row of the tile: the merge never reads it
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) *(f32x4 *)(po + dt * 16 + 4 * g) = o[dt][rt];
         if (g == 0) {
