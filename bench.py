@@ -198,8 +198,8 @@ def main():
     if os.path.exists(tpath):
         import hashlib
         t = json.load(open(tpath))
-        src = open(os.path.join(ROOT, "paper_2605_05802_amd", "csrc", "gemm.hip"), "rb").read()
-        if t.get("gemm_hip_sha1") == hashlib.sha1(src).hexdigest() and args.workload != "tiny":
+        src = open(os.path.join(ROOT, "paper_2605_05802_amd", "csrc", "gemm_stream.hip"), "rb").read()
+        if t.get("kernel_source_sha1") == hashlib.sha1(src).hexdigest() and args.workload != "tiny":
             traffic = t.get("gate_up_decode_bytes_per_launch")
 
     # whole decode step against the HBM roofline (un-profiled steps only)

@@ -95,6 +95,15 @@ enum GemmEpilogue {
     EPI_SWIGLU = 1  // packed rows alternate 16 gate / 16 up features; out = silu(gate)*up, bf16 fragment-major
 };
 
+// k-steps [*k0, *k1) of split sp when `units` groups of `unit` k-steps are dealt out evenly
+__device__ __forceinline__ void split_range(int ks_total, int unit, int splits, int sp, int *k0, int *k1) {
+    const int units = ks_total / unit, q = units / splits, r = units % splits;
+    const int u0 = sp * q + min(sp, r);
+    *k0 = u0 * unit;
+    *k1 = (u0 + q + (sp < r ? 1 : 0)) * unit;
+}
+
+
 struct GemmArgs {
     const uint4 *X;
     const uint4 *W;
@@ -110,6 +119,8 @@ struct GemmArgs {
     size_t split_stride; // EPI_F32: elements between consecutive splits
 };
 
+// The decode-time kernel with a loader wavefront (a.wide != 0, M <= 128); launch_gemm dispatches to it.
+int launch_gemm_stream(const GemmArgs &a, GemmEpilogue epi, hipStream_t stream);
 int launch_gemm(const GemmArgs &a, GemmEpilogue epi, hipStream_t stream);
 
 // ---------------------------------------------------------------------------------------------
