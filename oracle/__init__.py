@@ -73,6 +73,9 @@ def load(real: str = "double"):
         L.sro_gate_batch.argtypes = [vp, ci, ci, ci, vp, ci, cd, vp, vp]
         L.sro_advantage.restype = None
         L.sro_advantage.argtypes = [vp, ci, cd, vp]
+        L.sro_signals_batch.restype = None
+        L.sro_signals_batch.argtypes = [vp, vp, vp, ci, ci, ci, vp, ci, cd, cd, vp]
+        L.sro_lcm32.restype = ctypes.c_int64
         L.sro_model_new.restype = vp
         L.sro_model_new.argtypes = [ctypes.POINTER(_Shape), vp, vp, vp]
         L.sro_model_set_layer.restype = None
@@ -142,6 +145,35 @@ def gate_batch(actions, lens, d_L: float):
     load().sro_gate_batch(a.ctypes.data, n_groups, G, stride, lens.ctypes.data, len(lens), d_L,
                           sums.ctypes.data, cut.ctypes.data)
     return sums, cut
+
+
+SIGNALS_DTYPE = np.dtype([("d_K", "f8"), ("lev_scaled", "i8"), ("bigram_jaccard", "f8"), ("action_entropy", "f8"),
+                          ("unique_prefix", "i4"), ("n_at_step", "i4"), ("unique_action", "i4"), ("unique_obs", "i4"),
+                          ("n_done", "i4"), ("cut_d", "u1"), ("cut_or", "u1")], align=True)
+
+
+def lcm32() -> int:
+    """lcm(1..32): lev_scaled / lcm32() is the exact sum over pairs of lev / longer length."""
+    return int(load().sro_lcm32())
+
+
+def signals_batch(actions, lens, d_L: float, tau_H: float = 2.0, obs=None, end_step=None) -> np.ndarray:
+    """Appendix B signals and the gates of Eq. 2 / Eq. 3 at each step K in `lens`.
+
+    actions, obs: [n_groups, G, stride] ids; end_step: [n_groups, G] number of steps after which a member
+    finished (anything > stride while it is still running).  Returns a structured array [n_lens, n_groups].
+    """
+    a = _i32(actions)
+    n_groups, G, stride = a.shape
+    lens = _i32(lens)
+    o = _i32(obs) if obs is not None else None
+    e = _i32(end_step) if end_step is not None else None
+    out = np.zeros((len(lens), n_groups), dtype=SIGNALS_DTYPE)
+    assert SIGNALS_DTYPE.itemsize == 56
+    load().sro_signals_batch(a.ctypes.data, o.ctypes.data if o is not None else None,
+                             e.ctypes.data if e is not None else None, n_groups, G, stride, lens.ctypes.data,
+                             len(lens), d_L, tau_H, out.ctypes.data)
+    return out
 
 
 def advantage(r, eps: float = 1e-6) -> np.ndarray:

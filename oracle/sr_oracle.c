@@ -10,6 +10,11 @@
  *   - Gate: the paper's Section 3.2 signal d_K (mean over the C(G,2) pairs of
  *     the prefix edit distance divided by the longer length) and the decision
  *     of Eq. 2, cut iff d_K < d_L, evaluated in integers.
+ *   - The other in-group signals of Appendix B (action-bigram Jaccard, unique
+ *     prefix / action / observation counts, action entropy, termination
+ *     fraction), d_K for members that finished early (each pair divided by
+ *     the longer of its two prefix lengths) and the two-clause gate of
+ *     Appendix E (Eq. 3), decided in exact integer arithmetic.
  *   - Advantage: Eq. 1 (population standard deviation).
  *   - Decoder: pre-norm transformer decoder (RMSNorm, biased QKV projection,
  *     rotate-half RoPE, grouped-query causal attention, SwiGLU FFN, untied LM
@@ -20,6 +25,7 @@
  * (a second build with -DSRO_REAL=float exists to measure the precision scale).
  * Weights arrive as bf16 bit patterns and are widened exactly.
  */
+#include <limits.h>
 #include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
@@ -107,6 +113,144 @@ void sro_gate_batch(const int32_t *actions, int n_groups, int G, int stride,
         }
     }
 }
+
+/* ------------------------------------------------------------------------- */
+/* In-group divergence signals at step K (Appendix B) and the two-clause gate  */
+/* (Appendix E, Eq. 3), for groups whose members may have finished early.      */
+/* ------------------------------------------------------------------------- */
+/*
+ * Member i finished after end_step[i] environment steps (a large value while it
+ * is still running), so at step K it contributes the prefix a_i[0 : len_i] with
+ * len_i = min(K, end_step[i]).  A pair's edit distance is divided by the longer
+ * of its two prefix lengths (Section 3.2); a pair of two empty prefixes counts 0.
+ *
+ * The sum of the pair terms is also kept exactly, as an integer multiple of
+ * 1 / SRO_LCM32 where SRO_LCM32 = lcm(1..32): lev * (SRO_LCM32 / longer) summed
+ * over pairs.  Eq. 2 is then decided without rounding:
+ *   d_K < d_L  <=>  lev_scaled / (P * LCM) < num / 1e6  <=>  lev_scaled * 1e6 < num * P * LCM.
+ */
+#define SRO_LCM32 144403552893600LL
+
+typedef struct {
+    double d_K;               /* mean over pairs of lev / longer length                              */
+    int64_t lev_scaled;       /* sum over pairs of lev * (SRO_LCM32 / longer length)                 */
+    double bigram_jaccard;    /* mean over pairs of 1 - |A n B| / |A u B|, A, B = sets of action bigrams */
+    double action_entropy;    /* Shannon entropy (nats) of the step-K action over members at step K   */
+    int32_t unique_prefix;    /* distinct prefixes among the G members                                */
+    int32_t n_at_step;        /* members whose prefix reaches step K (len_i == K)                     */
+    int32_t unique_action;    /* distinct a_{i,K} among them                                          */
+    int32_t unique_obs;       /* distinct o_{i,K} among them                                          */
+    int32_t n_done;           /* members that had finished by step K (end_step <= K)                  */
+    uint8_t cut_d;            /* Eq. 2: d_K < d_L                                                     */
+    uint8_t cut_or;           /* Eq. 3: d_K < d_L or tau_K >= tau_H, tau_K = n_done / G               */
+} sro_signals_t;
+
+static int distinct_bigrams(const int32_t *a, int len, int32_t (*out)[2]) {
+    int n = 0;
+    for (int t = 0; t + 1 < len; ++t) {
+        int seen = 0;
+        for (int u = 0; u < n; ++u)
+            if (out[u][0] == a[t] && out[u][1] == a[t + 1]) seen = 1;
+        if (!seen) { out[n][0] = a[t]; out[n][1] = a[t + 1]; ++n; }
+    }
+    return n;
+}
+
+/* actions, obs: [G][stride] (obs may be NULL); end_step: [G] or NULL (nobody has finished). K <= 32, K <= stride. */
+void sro_signals(const int32_t *actions, const int32_t *obs, const int32_t *end_step, int G, int stride, int K,
+                 double d_L, double tau_H, sro_signals_t *out) {
+    int len[64];
+    int n_done = 0;
+    for (int i = 0; i < G; ++i) {
+        const int e = end_step ? end_step[i] : INT32_MAX;
+        len[i] = e < K ? e : K;
+        if (e <= K) ++n_done;
+    }
+    const int64_t P = (int64_t)G * (G - 1) / 2;
+
+    /* mean pairwise prefix edit distance, and the action-bigram Jaccard distance */
+    double dsum = 0.0, jsum = 0.0;
+    int64_t scaled = 0;
+    for (int i = 0; i < G; ++i)
+        for (int j = i + 1; j < G; ++j) {
+            const int32_t *a = actions + (size_t)i * stride, *b = actions + (size_t)j * stride;
+            const int longer = len[i] > len[j] ? len[i] : len[j];
+            if (longer > 0) {
+                const int d = sro_lev(a, len[i], b, len[j]);
+                dsum += (double)d / (double)longer;
+                scaled += (int64_t)d * (SRO_LCM32 / longer);
+            }
+            int32_t A[32][2], B[32][2];
+            const int na = distinct_bigrams(a, len[i], A), nb = distinct_bigrams(b, len[j], B);
+            int inter = 0;
+            for (int u = 0; u < na; ++u)
+                for (int v = 0; v < nb; ++v)
+                    if (A[u][0] == B[v][0] && A[u][1] == B[v][1]) ++inter;
+            const int uni = na + nb - inter;
+            jsum += uni > 0 ? 1.0 - (double)inter / (double)uni : 0.0;   /* two empty sets: identical */
+        }
+    out->d_K = dsum / (double)P;
+    out->lev_scaled = scaled;
+    out->bigram_jaccard = jsum / (double)P;
+
+    /* distinct prefixes */
+    int uniq = 0;
+    for (int i = 0; i < G; ++i) {
+        int dup = 0;
+        for (int j = 0; j < i; ++j)
+            if (len[j] == len[i] && memcmp(actions + (size_t)i * stride, actions + (size_t)j * stride,
+                                           (size_t)len[i] * sizeof(int32_t)) == 0)
+                dup = 1;
+        if (!dup) ++uniq;
+    }
+    out->unique_prefix = uniq;
+
+    /* the single step-K action / observation, over the members that reach step K */
+    int n_at = 0, ua = 0, uo = 0;
+    double H = 0.0;
+    for (int i = 0; i < G; ++i) n_at += len[i] == K;
+    for (int i = 0; i < G; ++i) {
+        if (len[i] != K) continue;
+        const int32_t ai = actions[(size_t)i * stride + K - 1];
+        int first_a = 1, first_o = 1, count = 0;
+        for (int j = 0; j < G; ++j) {
+            if (len[j] != K) continue;
+            const int same_a = actions[(size_t)j * stride + K - 1] == ai;
+            if (same_a) ++count;
+            if (j < i && same_a) first_a = 0;
+            if (obs && j < i && obs[(size_t)j * stride + K - 1] == obs[(size_t)i * stride + K - 1]) first_o = 0;
+        }
+        if (first_a) {
+            ++ua;
+            const double p = (double)count / (double)n_at;
+            H -= p * log(p);
+        }
+        if (obs && first_o) ++uo;
+    }
+    out->n_at_step = n_at;
+    out->unique_action = ua;
+    out->unique_obs = obs ? uo : 0;
+    out->action_entropy = H;
+    out->n_done = n_done;
+
+    const int64_t num_d = (int64_t)llround(d_L * 1e6), num_t = (int64_t)llround(tau_H * 1e6);
+    out->cut_d = (uint8_t)((__int128)scaled * 1000000 < (__int128)num_d * P * SRO_LCM32);
+    out->cut_or = (uint8_t)(out->cut_d || (int64_t)n_done * 1000000 >= num_t * G);
+}
+
+/* actions/obs [n_groups][G][stride], end_step [n_groups][G]; out [n_lens][n_groups] */
+void sro_signals_batch(const int32_t *actions, const int32_t *obs, const int32_t *end_step, int n_groups, int G,
+                       int stride, const int32_t *lens, int n_lens, double d_L, double tau_H, sro_signals_t *out) {
+    for (int li = 0; li < n_lens; ++li) {
+#pragma omp parallel for schedule(static)
+        for (int g = 0; g < n_groups; ++g)
+            sro_signals(actions + (size_t)g * G * stride, obs ? obs + (size_t)g * G * stride : NULL,
+                        end_step ? end_step + (size_t)g * G : NULL, G, stride, lens[li], d_L, tau_H,
+                        out + (size_t)li * n_groups + g);
+    }
+}
+
+int64_t sro_lcm32(void) { return SRO_LCM32; }
 
 /* ------------------------------------------------------------------------- */
 /* Group-relative advantage, Eq. 1                                            */
