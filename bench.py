@@ -105,6 +105,29 @@ def gate_throughput(sr, torch, synth, iters=20):
     return 65536 / (ms * 1e-3), ms, acts
 
 
+def signals_throughput(sr, torch, acts, iters=20):
+    """Appendix-B signals and the two-clause gate on the same 65536 groups, with early finishers."""
+    rng = np.random.default_rng(1)
+    n_groups, G, stride = acts.shape
+    obs = rng.integers(0, 3, size=acts.shape).astype(np.int32)
+    end = np.where(rng.random((n_groups, G)) < 0.35, rng.integers(1, stride + 1, size=(n_groups, G)),
+                   10 ** 6).astype(np.int32)
+    a, o, e = torch.from_numpy(acts).cuda(), torch.from_numpy(obs).cuda(), torch.from_numpy(end).cuda()
+    out = torch.zeros((3, n_groups, sr.SIGNALS_BYTES), dtype=torch.uint8, device="cuda")
+    lens = [5, 10, 15]
+    for _ in range(3):
+        sr.sr_signals_batch(a, lens, 0.12, 0.9, out, obs=o, end_step=e)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(iters):
+        sr.sr_signals_batch(a, lens, 0.12, 0.9, out, obs=o, end_step=e)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / iters
+    return n_groups / (ms * 1e-3), ms
+
+
 def cpu_baseline(synth, shape, acts, n_tokens=12):
     """The CPU checker, as it stands, on a bounded sample: n_tokens single-sequence token forwards at
     the benchmark's model shape (weights generated on the host by the same seeded generator), plus the
@@ -215,6 +238,7 @@ def main():
     step_ms = [ms for (m, ms) in zip(res["decode_meta"], res["step_ms"]) if not m[2]]
 
     gate_gps, gate_ms, acts = gate_throughput(sr, torch, synth)
+    sig_gps, sig_ms = signals_throughput(sr, torch, acts)
     out = {
         "metric": "decoded tokens/s at Qwen2.5-7B shape, G=8 (whole gated episode: prompt prefill, per-turn "
                   "observation prefill, greedy decode, gate, compaction)",

@@ -178,6 +178,50 @@ int sr_retire_and_compact(sr_ctx *ctx, int *host_n_live_groups, void *stream);
 int sr_gate_batch(const int32_t *actions, int n_groups, int G, int stride, const int *prefix_lens,
                   int n_lens, double threshold, int32_t *sums, uint8_t *retire, void *stream);
 
+/*
+ * The in-group divergence signals of Appendix B at step K, and the gates of Eq. 2 and of
+ * Appendix E (Eq. 3), for groups whose members may have finished early (no context needed).
+ *
+ * Member i of a group finished after end_step[i] environment steps (any value > stride while
+ * it is still running; values below 0 count as 0), so at step K it contributes the prefix
+ * a_i[0 : len_i], len_i = min(K, end_step[i]).
+ *   d_K            mean over the C(G,2) pairs of the Levenshtein distance of the two prefixes
+ *                  divided by the longer of their lengths (Section 3.2); a pair of empty
+ *                  prefixes counts 0
+ *   lev_scaled     the same sum before the division by C(G,2), exact, in units of
+ *                  1 / lcm(1..32) = 1 / 144403552893600
+ *   bigram_jaccard mean over pairs of 1 - |A n B| / |A u B|, A and B the SETS of consecutive
+ *                  action pairs of the two prefixes; two empty sets count as identical (0)
+ *   unique_prefix  number of distinct prefixes among the G members (the ratio is this / G)
+ *   n_at_step      members whose prefix reaches step K; the next three are taken over them
+ *   unique_action  distinct step-K actions a_{i,K}; unique_obs: distinct step-K observation
+ *                  ids o_{i,K} (0 if obs is NULL); action_entropy: Shannon entropy of the
+ *                  step-K action, natural logarithm
+ *   n_done         members that had finished by step K (end_step <= K); tau_K = n_done / G
+ *   cut_d          d_K < d_L (Eq. 2, strict), decided in integers with d_L read as
+ *                  round(d_L * 1e6) / 1e6;  cut_or: cut_d or tau_K >= tau_H (Eq. 3), tau_H
+ *                  read the same way (a tau_H above 1 switches the second clause off)
+ * Pair terms are added in the order (0,1), (0,2), ..., (G-2,G-1), so d_K and bigram_jaccard
+ * are reproducible bit for bit.
+ *
+ * actions, obs: device int32 [n_groups][G][stride] (obs may be NULL); end_step: device int32
+ * [n_groups][G] or NULL (nobody has finished); prefix_lens: HOST int [n_lens], each in
+ * [1, min(stride, 32)]; out: device [n_lens][n_groups].  2 <= G <= 16, n_lens <= 8.
+ * SR_E_ARG on anything else.  Asynchronous on `stream`; the caller owns every buffer.
+ */
+typedef struct {
+    double d_K;
+    int64_t lev_scaled;
+    double bigram_jaccard;
+    double action_entropy;
+    int32_t unique_prefix, n_at_step, unique_action, unique_obs, n_done;
+    uint8_t cut_d, cut_or;
+    uint8_t reserved[2];
+} sr_signals_t;
+int sr_signals_batch(const int32_t *actions, const int32_t *obs, const int32_t *end_step, int n_groups, int G,
+                     int stride, const int *prefix_lens, int n_lens, double d_L, double tau_H,
+                     sr_signals_t *out, void *stream);
+
 /* Overwrite the action ids of turn `turn` (1-based) for all live sequences:
  * ids is device int32 [n_live_seq].  For action_mod == 0, or for tests. */
 int sr_set_actions(sr_ctx *ctx, int turn, const int32_t *ids, void *stream);

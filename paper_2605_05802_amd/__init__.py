@@ -17,7 +17,7 @@ SR_OK, SR_E_ARG, SR_E_NOMEM, SR_E_STATE, SR_E_HIP = 0, -1, -2, -3, -4
 
 EXPORTS = ("sr_init", "sr_destroy", "sr_load_weights", "sr_prefill_chunk", "sr_decode_step", "sr_gate",
            "sr_retire_and_compact", "sr_gate_batch", "sr_set_actions", "sr_get_actions", "sr_get_logits",
-           "sr_get_live_map", "sr_stats", "sr_strerror", "sr_profile", "sr_profile_read")
+           "sr_get_live_map", "sr_stats", "sr_strerror", "sr_profile", "sr_profile_read", "sr_signals_batch")
 
 KERNEL_CLASSES = ("norm", "gemm_qkv", "qkv_post", "attn_decode", "attn_prefill", "attn_merge",
                   "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm_head", "argmax")
@@ -84,6 +84,8 @@ def lib():
         L.sr_gate.argtypes = [vp, ci, vp, vp, vp]
         L.sr_retire_and_compact.argtypes = [vp, ctypes.POINTER(ci), vp]
         L.sr_gate_batch.argtypes = [vp, ci, ci, ci, ctypes.POINTER(ci), ci, ctypes.c_double, vp, vp, vp]
+        L.sr_signals_batch.argtypes = [vp, vp, vp, ci, ci, ci, ctypes.POINTER(ci), ci, ctypes.c_double,
+                                       ctypes.c_double, vp, vp]
         L.sr_set_actions.argtypes = [vp, ci, vp, vp]
         L.sr_get_actions.argtypes = [vp, vp, vp]
         L.sr_get_logits.argtypes = [vp, vp, vp]
@@ -131,6 +133,21 @@ def sr_gate_batch(actions, prefix_lens, threshold: float, sums=None, retire=None
     lens = (ctypes.c_int * len(prefix_lens))(*prefix_lens)
     _check(lib().sr_gate_batch(_ptr(actions), n_groups, G, stride, lens, len(prefix_lens), threshold,
                                _ptr(sums), _ptr(retire), _stream(stream)), "sr_gate_batch")
+
+
+SIGNALS_BYTES = 56       # sizeof(sr_signals_t)
+SIGNALS_FIELDS = (("d_K", "f8"), ("lev_scaled", "i8"), ("bigram_jaccard", "f8"), ("action_entropy", "f8"),
+                  ("unique_prefix", "i4"), ("n_at_step", "i4"), ("unique_action", "i4"), ("unique_obs", "i4"),
+                  ("n_done", "i4"), ("cut_d", "u1"), ("cut_or", "u1"), ("reserved", "u1", (2,)))
+
+
+def sr_signals_batch(actions, prefix_lens, d_L: float, tau_H: float, out, obs=None, end_step=None, stream=None):
+    """actions, obs: device int32 [n_groups, G, stride]; end_step: device int32 [n_groups, G];
+    out: device uint8 [n_lens, n_groups, SIGNALS_BYTES] receiving sr_signals_t records."""
+    n_groups, G, stride = actions.shape
+    lens = (ctypes.c_int * len(prefix_lens))(*prefix_lens)
+    _check(lib().sr_signals_batch(_ptr(actions), _ptr(obs), _ptr(end_step), n_groups, G, stride, lens,
+                                  len(prefix_lens), d_L, tau_H, _ptr(out), _stream(stream)), "sr_signals_batch")
 
 
 class Context:
