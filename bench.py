@@ -258,6 +258,8 @@ def main():
                         "decode_only_tokens_per_s": decoded / (sum(res["step_ms"]) * 1e-3)},
         "kernel_ms_per_profiled_step": {k: v[1] / max(len(rows), 1) for k, v in res["kernel_times"].items()},
         "gate": {"groups_per_s": gate_gps, "ms_per_launch": gate_ms, "workload": "65536 groups x G=8, prefixes 5/10/15"},
+        "signals": {"groups_per_s": sig_gps, "ms_per_launch": sig_ms,
+                    "workload": "same groups, 35 % of members finished early: Appendix-B signals + two-clause gate"},
         "episode": {k: res["stats"][k] for k in ("decoded_tokens", "prefill_tokens", "groups_retired", "pages_freed",
                                                 "n_live_groups")},
         "paper_context": "paper reports wall-clock only (vLLM on RTX 6000 Ada): ~95% of time in rollout, ~40% "

@@ -73,6 +73,10 @@ def load(real: str = "double"):
         L.sro_gate_batch.argtypes = [vp, ci, ci, ci, vp, ci, cd, vp, vp]
         L.sro_advantage.restype = None
         L.sro_advantage.argtypes = [vp, ci, cd, vp]
+        L.sro_logprob.restype = cd
+        L.sro_logprob.argtypes = [vp, ci, ctypes.c_int32]
+        L.sro_grpo_loss.restype = cd
+        L.sro_grpo_loss.argtypes = [vp, vp, ci, ci, cd, vp]
         L.sro_signals_batch.restype = None
         L.sro_signals_batch.argtypes = [vp, vp, vp, ci, ci, ci, vp, ci, cd, cd, vp]
         L.sro_lcm32.restype = ctypes.c_int64
@@ -279,6 +283,38 @@ def sample(logits, temperature: float, seed: int, orig_seq: int, pos: int):
 # ----------------------------------------------------------------------------
 # gated group rollout (Appendix C.1)
 # ----------------------------------------------------------------------------
+def logprob(logits, target: int) -> float:
+    """log softmax(logits)[target] (logits as returned by Seq.forward)."""
+    lg = np.ascontiguousarray(logits)
+    real = "float" if lg.dtype == np.float32 else "double"
+    return float(load(real).sro_logprob(lg.ctypes.data, len(lg), int(target)))
+
+
+def score(seq: "Seq", last_logits, tokens, mask=None):
+    """Teacher-forced pass over `tokens` appended to `seq` (Appendix C.2).
+
+    last_logits: logits at the sequence's current last position (they predict tokens[0]).
+    Returns (per-token log-probabilities, with 0 where mask is 0; logits at the new last position).
+    """
+    tokens = _i32(tokens)
+    lp = np.zeros(len(tokens))
+    logits = last_logits
+    for j, tok in enumerate(tokens):
+        if mask is None or mask[j]:
+            lp[j] = logprob(logits, tok)
+        logits = seq.forward([tok])
+    return lp, logits
+
+
+def grpo_loss(logprob_seq, rewards, G: int, eps: float = 1e-6):
+    """(-(1/N) sum_i A_i log p(tau_i), advantages) for [n_groups*G] sequence log-likelihoods and rewards."""
+    lp = np.ascontiguousarray(logprob_seq, dtype=np.float64)
+    r = np.ascontiguousarray(rewards, dtype=np.float64)
+    A = np.empty_like(r)
+    loss = load().sro_grpo_loss(lp.ctypes.data, r.ctypes.data, len(r) // G, G, eps, A.ctypes.data)
+    return float(loss), A
+
+
 def run_episode(model: Model, prompts, obs_fn, G: int, turns: int, act_len: int, action_mod: int,
                 gate_turns, d_L: float, keep_logits: bool = False, temperature: float = 0.0, sample_seed: int = 0):
     """Rolls every group forward turn by turn, gating at the given turns.

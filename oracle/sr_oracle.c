@@ -15,7 +15,9 @@
  *     fraction), d_K for members that finished early (each pair divided by
  *     the longer of its two prefix lengths) and the two-clause gate of
  *     Appendix E (Eq. 3), decided in exact integer arithmetic.
- *   - Advantage: Eq. 1 (population standard deviation).
+ *   - Advantage: Eq. 1 (population standard deviation); the teacher-forced
+ *     log-likelihood of Appendix C.2 (log-softmax at action-token positions)
+ *     and the policy-gradient loss built from the two.
  *   - Decoder: pre-norm transformer decoder (RMSNorm, biased QKV projection,
  *     rotate-half RoPE, grouped-query causal attention, SwiGLU FFN, untied LM
  *     head), one token at a time over a flat per-sequence KV list.  No paging,
@@ -535,6 +537,32 @@ int sro_sample(const real *logits, int V, double temperature, uint64_t seed, int
     }
     if (top2_gap) *top2_gap = best_s - second;
     return best;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Teacher-forced log-likelihood (Appendix C.2) and the policy-gradient loss   */
+/* ------------------------------------------------------------------------- */
+/* log softmax(logits)[target]: the largest logit is subtracted before the exponentials. */
+double sro_logprob(const real *logits, int V, int32_t target) {
+    real mx = logits[0];
+    for (int v = 1; v < V; ++v)
+        if (logits[v] > mx) mx = logits[v];
+    double sum = 0.0;
+    for (int v = 0; v < V; ++v) sum += exp((double)(logits[v] - mx));
+    return (double)(logits[target] - mx) - log(sum);
+}
+
+/*
+ * L = -(1/N) sum_i A_i log p(tau_i) over the N = n_groups * G trajectories of the batch, with the
+ * group-relative advantages of Eq. 1 (Section 2.1).  logprob, rewards, A: [n_groups][G].
+ */
+double sro_grpo_loss(const double *logprob, const double *rewards, int n_groups, int G, double eps, double *A) {
+    double acc = 0.0;
+    for (int g = 0; g < n_groups; ++g) {
+        sro_advantage(rewards + (size_t)g * G, G, eps, A + (size_t)g * G);
+        for (int i = 0; i < G; ++i) acc += A[(size_t)g * G + i] * logprob[(size_t)g * G + i];
+    }
+    return -acc / ((double)n_groups * G);
 }
 
 /* Greedy choice: lowest index among the maxima.  Also reports the gap to the runner-up. */
