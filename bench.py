@@ -88,6 +88,49 @@ def run_episode(sr, torch, synth, shape, cfg, weights, turns, seed, profile_step
             "kernel_times": kernel_times, "shared_tokens": (cfg.prompt_len // 64) * 64}
 
 
+def score_pass(sr, torch, synth, shape, cfg, weights, turns, seed):
+    """Teacher-forced log-likelihood pass (Appendix C.2) over trajectories of the benchmark's shape: prompt and
+    observations go through sr_prefill_chunk, the action tokens of every turn through sr_score_chunk."""
+    G = cfg.G
+    max_len = cfg.prompt_len + cfg.turns * (cfg.obs_len + cfg.act_len)
+    kv_tokens = cfg.n_groups * cfg.prompt_len + cfg.n_groups * G * (max_len - cfg.prompt_len + 64)
+    pool = int(kv_tokens * kv_bytes_per_token(shape) * 1.05) + (64 << 20)
+    ctx = sr.Context(shape, cfg.n_groups, G, cfg.threshold, page_tokens=64, max_seq_len=max_len,
+                     max_turns=cfg.turns, action_mod=cfg.action_mod, kv_pool_bytes=pool)
+    embed, lm, fn, layers = weights
+    ctx.sr_load_weights(embed, lm, fn, layers)
+    conv = synth.converging_groups(cfg, seed)
+    prompts = torch.from_numpy(synth.prompts(cfg, shape.vocab, seed)).cuda()
+    n_seq = cfg.n_groups * G
+    gen = torch.Generator(device="cuda").manual_seed(seed)
+    ctx.sr_prefill_chunk(prompts, True)
+    obs_all = [torch.from_numpy(synth.observations(cfg, shape.vocab, seed, t, conv)).cuda() for t in range(turns)]
+    acts_all = [torch.randint(0, shape.vocab, (n_seq, cfg.act_len), dtype=torch.int32, device="cuda", generator=gen)
+                for _ in range(turns)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    score_ms = 0.0
+    evs = []
+    for t in range(turns):
+        ctx.sr_prefill_chunk(obs_all[t], False)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        ctx.sr_score_chunk(acts_all[t])
+        e1.record()
+        evs.append((e0, e1))
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    score_ms = sum(a.elapsed_time(b) for a, b in evs)
+    ctx.close()
+    n_act = n_seq * cfg.act_len * turns
+    flops_lm = 2.0 * shape.hidden * shape.vocab * n_act
+    flops_body = 2.0 * (weight_bytes_per_step(shape) / 2 - shape.hidden * shape.vocab) * n_act
+    return {"action_tokens": n_act, "action_tokens_per_s": n_act / wall, "wall_s": wall,
+            "score_calls_ms": score_ms, "score_calls_TFLOPs": (flops_lm + flops_body) / (score_ms * 1e-3) / 1e12,
+            "note": "wall includes the observation prefills; score_calls_* cover sr_score_chunk only "
+                    "(transformer body + LM head on every action row + log-softmax gather)"}
+
+
 def gate_throughput(sr, torch, synth, iters=20):
     acts, _ = synth.gate_actions(65536, 8, 30, 64, seed=0)
     a = torch.from_numpy(acts).cuda()
@@ -204,6 +247,7 @@ def main():
     if args.warmup > 0:
         run_episode(sr, torch, synth, shape, cfg, weights, min(args.warmup, cfg.turns), 0, None)
     res = run_episode(sr, torch, synth, shape, cfg, weights, turns, 0, profile_step=cfg.act_len // 2)
+    score = score_pass(sr, torch, synth, shape, cfg, weights, turns, 0) if args.layers == 0 else None
     del weights
     torch.cuda.empty_cache()
 
@@ -258,6 +302,7 @@ def main():
                         "decode_only_tokens_per_s": decoded / (sum(res["step_ms"]) * 1e-3)},
         "kernel_ms_per_profiled_step": {k: v[1] / max(len(rows), 1) for k, v in res["kernel_times"].items()},
         "gate": {"groups_per_s": gate_gps, "ms_per_launch": gate_ms, "workload": "65536 groups x G=8, prefixes 5/10/15"},
+        "score_pass": score,
         "signals": {"groups_per_s": sig_gps, "ms_per_launch": sig_ms,
                     "workload": "same groups, 35 % of members finished early: Appendix-B signals + two-clause gate"},
         "episode": {k: res["stats"][k] for k in ("decoded_tokens", "prefill_tokens", "groups_retired", "pages_freed",

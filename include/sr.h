@@ -179,6 +179,40 @@ int sr_gate_batch(const int32_t *actions, int n_groups, int G, int stride, const
                   int n_lens, double threshold, int32_t *sums, uint8_t *retire, void *stream);
 
 /*
+ * Teacher-forced scoring (Appendix C.2).  Appends chunk_len given tokens to every live sequence
+ * exactly like sr_prefill_chunk(..., shared_per_group = 0) -- their K/V are computed and the
+ * logits at the chunk's last position are kept -- and adds, for every chunk position t whose
+ * action_mask entry is non-zero, log softmax(logits at the position before t)[tokens[t]] to the
+ * sequence's running log-likelihood  log p(tau) = sum over action-token positions.  The logits
+ * at position t-1 predict the token at position t; the chunk's first token is predicted by the
+ * logits the previous prefill / scoring / decode call left, so the context must not be empty
+ * (SR_E_STATE).  Observation tokens are either passed with mask 0 or, cheaper, appended with
+ * sr_prefill_chunk, which computes no LM head for them.
+ *
+ * tokens: device int32 [n_live_seq][chunk_len]; action_mask: device uint8, same shape, or NULL
+ * (every token counts); out_token_logprob: device float [n_live_seq][chunk_len] receiving the
+ * per-token values (0 where masked), or NULL.  Arithmetic: bf16 operands, fp32 accumulation and
+ * fp32 log-sum-exp per row; the per-sequence sums are kept in double, added in token order.
+ * The running sums follow their sequences through sr_retire_and_compact.
+ */
+int sr_score_chunk(sr_ctx *ctx, const int32_t *tokens, const uint8_t *action_mask, int chunk_len,
+                   float *out_token_logprob, void *stream);
+
+/* Copy the running log-likelihoods of the live sequences to dst: device double [n_live_seq]. */
+int sr_get_logprob(sr_ctx *ctx, double *dst, void *stream);
+
+/*
+ * Policy-gradient loss of Section 2.1:  L = -(1/N) sum_i A_i log p(tau_i)  over the N = n_groups * G
+ * trajectories, with the group-relative advantages of Eq. 1 (population standard deviation;
+ * every advantage of a group whose rewards are all equal is exactly 0).  No context needed.
+ * logprob: device double [n_groups][G]; rewards: device float [n_groups][G]; advantages: device
+ * float [n_groups][G] or NULL; group_scratch: device double [n_groups], overwritten; loss: device
+ * double [1].  Groups are added in index order, so the result is reproducible.
+ */
+int sr_grpo_loss(const double *logprob, const float *rewards, int n_groups, int G, double eps,
+                 float *advantages, double *group_scratch, double *loss, void *stream);
+
+/*
  * The in-group divergence signals of Appendix B at step K, and the gates of Eq. 2 and of
  * Appendix E (Eq. 3), for groups whose members may have finished early (no context needed).
  *

@@ -17,7 +17,8 @@ SR_OK, SR_E_ARG, SR_E_NOMEM, SR_E_STATE, SR_E_HIP = 0, -1, -2, -3, -4
 
 EXPORTS = ("sr_init", "sr_destroy", "sr_load_weights", "sr_prefill_chunk", "sr_decode_step", "sr_gate",
            "sr_retire_and_compact", "sr_gate_batch", "sr_set_actions", "sr_get_actions", "sr_get_logits",
-           "sr_get_live_map", "sr_stats", "sr_strerror", "sr_profile", "sr_profile_read", "sr_signals_batch")
+           "sr_get_live_map", "sr_stats", "sr_strerror", "sr_profile", "sr_profile_read", "sr_signals_batch",
+           "sr_score_chunk", "sr_get_logprob", "sr_grpo_loss")
 
 KERNEL_CLASSES = ("norm", "gemm_qkv", "qkv_post", "attn_decode", "attn_prefill", "attn_merge",
                   "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm_head", "argmax")
@@ -86,6 +87,9 @@ def lib():
         L.sr_gate_batch.argtypes = [vp, ci, ci, ci, ctypes.POINTER(ci), ci, ctypes.c_double, vp, vp, vp]
         L.sr_signals_batch.argtypes = [vp, vp, vp, ci, ci, ci, ctypes.POINTER(ci), ci, ctypes.c_double,
                                        ctypes.c_double, vp, vp]
+        L.sr_score_chunk.argtypes = [vp, vp, vp, ci, vp, vp]
+        L.sr_get_logprob.argtypes = [vp, vp, vp]
+        L.sr_grpo_loss.argtypes = [vp, vp, ci, ci, ctypes.c_double, vp, vp, vp, vp]
         L.sr_set_actions.argtypes = [vp, ci, vp, vp]
         L.sr_get_actions.argtypes = [vp, vp, vp]
         L.sr_get_logits.argtypes = [vp, vp, vp]
@@ -150,6 +154,14 @@ def sr_signals_batch(actions, prefix_lens, d_L: float, tau_H: float, out, obs=No
                                   len(prefix_lens), d_L, tau_H, _ptr(out), _stream(stream)), "sr_signals_batch")
 
 
+def sr_grpo_loss(logprob, rewards, G: int, eps: float, advantages, group_scratch, loss, stream=None):
+    """logprob: device float64 [n_groups*G]; rewards: device float32, same; advantages: device float32 or None;
+    group_scratch: device float64 [n_groups]; loss: device float64 [1]."""
+    n_groups = logprob.numel() // G
+    _check(lib().sr_grpo_loss(_ptr(logprob), _ptr(rewards), n_groups, G, eps, _ptr(advantages), _ptr(group_scratch),
+                              _ptr(loss), _stream(stream)), "sr_grpo_loss")
+
+
 class Context:
     """Owns one sr_ctx.  Methods mirror the C entry points one to one."""
 
@@ -188,6 +200,13 @@ class Context:
     def sr_prefill_chunk(self, tokens, shared_per_group: bool, stream=None):
         _check(lib().sr_prefill_chunk(self._h, _ptr(tokens), tokens.shape[-1], int(shared_per_group),
                                       _stream(stream)), "sr_prefill_chunk")
+
+    def sr_score_chunk(self, tokens, action_mask=None, out_token_logprob=None, stream=None):
+        _check(lib().sr_score_chunk(self._h, _ptr(tokens), _ptr(action_mask), tokens.shape[-1],
+                                    _ptr(out_token_logprob), _stream(stream)), "sr_score_chunk")
+
+    def sr_get_logprob(self, dst, stream=None):
+        _check(lib().sr_get_logprob(self._h, _ptr(dst), _stream(stream)), "sr_get_logprob")
 
     def sr_decode_step(self, forced=None, out_tokens=None, stream=None):
         _check(lib().sr_decode_step(self._h, _ptr(forced), _ptr(out_tokens), _stream(stream)), "sr_decode_step")

@@ -33,6 +33,7 @@ struct LayerW {
 };
 
 constexpr int kMaxSplitK = 16;
+constexpr int kScoreRows = 2048;         // rows of the LM head computed at a time when every position is scored
 constexpr int kMaxAttnSplits = 16;
 
 }  // namespace
@@ -73,6 +74,9 @@ struct sr_ctx {
     int32_t *d_actions[2] = {nullptr, nullptr};
     int32_t *d_orig[2] = {nullptr, nullptr};   // original sequence id of every live row (keys the sampler)
     float *d_logits[2] = {nullptr, nullptr};
+    double *d_logprob[2] = {nullptr, nullptr};  // running teacher-forced log-likelihood of every live row
+    float *d_tok_lp = nullptr;                  // per-token values of the chunk being scored [n_seq0][max_seq_len]
+    float *score_logits = nullptr;              // [kScoreRows][vocab], allocated by the first scoring call
     int cur = 0;
     int32_t *d_greedy = nullptr, *d_chosen = nullptr, *d_sums = nullptr, *d_rows = nullptr;
     uint8_t *d_retire = nullptr;
@@ -264,6 +268,10 @@ struct Pass {
     bool want_logits;
     int logit_dup;       // output rows per unit (G for a shared chunk, else 1)
     int logit_row0;      // first output row in the logits buffer
+    // teacher-forced scoring: every row's logits give the log-probability of the next token of the chunk
+    bool score;
+    const uint8_t *score_mask;
+    int score_chunk_len, score_unit0;
 };
 
 int gemm(sr_ctx *c, const uint4 *X, const PackedMat &W, int M, GemmEpilogue epi, void *out, int ld_out,
@@ -456,6 +464,44 @@ int forward(sr_ctx *c, const Pass &p, hipStream_t st) {
         part_stride = (size_t)round_up(M, 128) * H;
     }
 
+    if (p.score) {
+        // final norm of every row, then the LM head kScoreRows rows at a time; each block of logits is
+        // reduced to one log-probability per row before the next block overwrites it
+        NormArgs na{};
+        na.resid = c->resid;
+        na.partials = c->partials;
+        na.n_partials = n_part;
+        na.partial_stride = part_stride;
+        na.gain = c->final_norm;
+        na.out = c->xn;
+        na.rows_out = M;
+        na.src_dup = 1;
+        na.src_stride = 1;
+        na.src_off = 0;
+        na.write_resid = 0;
+        na.H = H;
+        na.mt_total = c->mt_total;
+        na.eps = s.rms_eps;
+        SR_TRY(timed(c, SR_KC_NORM, st, [&] { return launch_resid_norm(na, st); }));
+        for (int r0 = 0; r0 < M; r0 += kScoreRows) {
+            const int blk = M - r0 < kScoreRows ? M - r0 : kScoreRows;
+            const uint4 *x = c->xn + (size_t)(r0 / 16) * 64;      // row tile r0 / 16 of every k-step
+            SR_TRY(timed(c, SR_KC_GEMM_LM_HEAD, st,
+                         [&] { return gemm(c, x, c->lm, blk, EPI_F32, c->score_logits, s.vocab, nullptr, st); }));
+            LogprobArgs la{};
+            la.logits = c->score_logits;
+            la.vocab = s.vocab;
+            la.tokens = p.tokens;
+            la.mask = p.score_mask;
+            la.chunk_len = p.score_chunk_len;
+            la.rows_per_unit = p.chunk;
+            la.row0 = r0;
+            la.tok0 = p.tok_off + 1;                              // a row predicts the token after it
+            la.out = c->d_tok_lp + (size_t)p.score_unit0 * p.score_chunk_len;
+            SR_TRY(timed(c, SR_KC_ARGMAX, st, [&] { return launch_logprob_rows(la, blk, st); }));
+        }
+    }
+
     if (p.want_logits) {
         NormArgs na{};
         na.resid = c->resid;
@@ -573,6 +619,8 @@ static int init_impl(sr_ctx *c) {
         SR_TRY(dev_alloc(c, &c->d_logits[i], (size_t)c->n_seq0 * s.vocab));
         SR_TRY(launch_fill_i32(c->d_actions[i], (size_t)c->n_seq0 * o.max_turns, -1, nullptr));
         SR_TRY(dev_alloc(c, &c->d_orig[i], (size_t)c->n_seq0));
+        SR_TRY(dev_alloc(c, &c->d_logprob[i], (size_t)c->n_seq0));
+        SR_HIP(hipMemset(c->d_logprob[i], 0, (size_t)c->n_seq0 * sizeof(double)));
     }
     {
         std::vector<int32_t> ids(c->n_seq0);
@@ -728,6 +776,79 @@ int sr_prefill_chunk(sr_ctx *c, const int32_t *tokens, int chunk_len, int shared
     return SR_OK;
 }
 
+int sr_score_chunk(sr_ctx *c, const int32_t *tokens, const uint8_t *action_mask, int chunk_len,
+                   float *out_token_logprob, void *stream) {
+    if (!c || !tokens || chunk_len <= 0) return SR_E_ARG;
+    if (!c->weights_loaded || !c->have_logits || c->seq_len == 0) return SR_E_STATE;
+    if (c->n_live_groups == 0) return SR_OK;
+    if (c->seq_len + chunk_len > c->o.max_seq_len) return SR_E_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    const sr_model_shape &s = c->s;
+    const int n = c->n_live_seq();
+    if (!c->score_logits) SR_TRY(dev_alloc(c, &c->score_logits, (size_t)kScoreRows * s.vocab));
+    if (!c->d_tok_lp) SR_TRY(dev_alloc(c, &c->d_tok_lp, (size_t)c->n_seq0 * c->o.max_seq_len));
+    const int new_len = c->seq_len + chunk_len;
+    SR_TRY(grow_pages(c, new_len, false, st));
+
+    // the chunk's first token is predicted by the logits of the position before the chunk
+    {
+        LogprobArgs la{};
+        la.logits = c->d_logits[c->cur];
+        la.vocab = s.vocab;
+        la.tokens = tokens;
+        la.mask = action_mask;
+        la.chunk_len = chunk_len;
+        la.row0 = 0;
+        la.rows_per_unit = 1;
+        la.tok0 = 0;
+        la.out = c->d_tok_lp;
+        SR_TRY(launch_logprob_rows(la, n, st));
+    }
+    for (int c0 = 0; c0 < chunk_len; c0 += c->R) {
+        const int cl = chunk_len - c0 < c->R ? chunk_len - c0 : c->R;
+        const int upp = c->R / cl;                 // units per pass
+        for (int u0 = 0; u0 < n; u0 += upp) {
+            const int nu = n - u0 < upp ? n - u0 : upp;
+            Pass p{};
+            p.rows = nu * cl;
+            p.n_units = nu;
+            p.chunk = cl;
+            p.pos0 = c->seq_len + c0;
+            p.pt_row0 = u0;
+            p.pt_row_stride = 1;
+            p.tokens = tokens + (size_t)u0 * chunk_len;
+            p.tok_stride = chunk_len;
+            p.tok_off = c0;
+            p.decode = false;
+            p.want_logits = (c0 + cl == chunk_len);
+            p.logit_dup = 1;
+            p.logit_row0 = u0;
+            p.score = true;
+            p.score_mask = action_mask ? action_mask + (size_t)u0 * chunk_len : nullptr;
+            p.score_chunk_len = chunk_len;
+            p.score_unit0 = u0;
+            SR_TRY(forward(c, p, st));
+        }
+    }
+    SR_TRY(launch_accumulate_logprob(c->d_tok_lp, n, chunk_len, c->d_logprob[c->cur], st));
+    if (out_token_logprob)
+        SR_HIP(hipMemcpyAsync(out_token_logprob, c->d_tok_lp, (size_t)n * chunk_len * sizeof(float),
+                              hipMemcpyDeviceToDevice, st));
+    c->seq_len = new_len;
+    c->st.prefill_tokens += (int64_t)n * chunk_len;
+    c->have_logits = true;
+    return SR_OK;
+}
+
+int sr_get_logprob(sr_ctx *c, double *dst, void *stream) {
+    if (!c || !dst) return SR_E_ARG;
+    const int n = c->n_live_seq();
+    if (n == 0) return SR_OK;
+    SR_HIP(hipMemcpyAsync(dst, c->d_logprob[c->cur], (size_t)n * sizeof(double), hipMemcpyDeviceToDevice,
+                          (hipStream_t)stream));
+    return SR_OK;
+}
+
 int sr_decode_step(sr_ctx *c, const int32_t *forced, int32_t *out_tokens, void *stream) {
     if (!c) return SR_E_ARG;
     if (!c->weights_loaded || !c->have_logits) return SR_E_STATE;
@@ -828,6 +949,7 @@ int sr_retire_and_compact(sr_ctx *c, int *host_n_live_groups, void *stream) {
                                       (size_t)c->o.max_turns * 4, st));
             SR_TRY(launch_gather_rows(c->d_logits[nxt], c->d_logits[c->cur], c->d_rows, n, (size_t)c->s.vocab * 4, st));
             SR_TRY(launch_gather_rows(c->d_orig[nxt], c->d_orig[c->cur], c->d_rows, n, 4, st));
+            SR_TRY(launch_gather_rows(c->d_logprob[nxt], c->d_logprob[c->cur], c->d_rows, n, 8, st));
             c->cur = nxt;
             SR_HIP(hipStreamSynchronize(st));     // h_rows may be rewritten by the next compaction
         }

@@ -207,6 +207,26 @@ int launch_attn_merge(const AttnArgs &a, const AttnPhase *phases, int n_phases, 
                       int mt_total, hipStream_t stream);
 
 // ---------------------------------------------------------------------------------------------
+// teacher-forced scoring
+// ---------------------------------------------------------------------------------------------
+// Row r of `logits` is row row0 + r of a pass whose units hold rows_per_unit consecutive rows each: it
+// belongs to unit (row0 + r) / rows_per_unit and gives the distribution of chunk token
+// tok0 + (row0 + r) % rows_per_unit of that unit; out[unit][token] = log softmax(row)[tokens[unit][token]],
+// or 0 where mask[unit][token] == 0.  Rows whose token index is >= chunk_len are skipped.
+struct LogprobArgs {
+    const float *logits;     // [rows][vocab]
+    int vocab;
+    const int32_t *tokens;   // [units][chunk_len]
+    const uint8_t *mask;     // [units][chunk_len] or null
+    int chunk_len;
+    int row0, rows_per_unit, tok0;
+    float *out;              // [units][chunk_len]
+};
+int launch_logprob_rows(const LogprobArgs &a, int rows, hipStream_t stream);
+// logprob[u] += sum over t of tok_lp[u][t], in token order
+int launch_accumulate_logprob(const float *tok_lp, int n_seq, int chunk_len, double *logprob, hipStream_t stream);
+
+// ---------------------------------------------------------------------------------------------
 // misc
 // ---------------------------------------------------------------------------------------------
 int launch_fill_i32(int32_t *dst, size_t n, int32_t value, hipStream_t stream);
