@@ -70,6 +70,9 @@ typedef struct {
                                 (sample_seed, original sequence id, position of the token): reproducible, and
                                 independent of where the sequence sits in the batch */
     uint64_t sample_seed;
+    float tau_H;             /* 0 = the one-clause gate of Eq. 2; > 0 = sr_gate also retires a group when the
+                                fraction of its members that have finished (sr_finish_sequences) is >= tau_H
+                                (Appendix E, Eq. 3) */
 } sr_options;
 
 /* bf16 device pointers; borrowed only for the duration of sr_load_weights. */
@@ -97,6 +100,8 @@ typedef struct {
     int32_t groups_retired;   /* total over all gates so far */
     int32_t pages_freed;      /* total over all gates so far */
     int32_t cow_page_copies;  /* pages duplicated because a member appended into a shared page */
+    int32_t seqs_finished;    /* sequences taken out by sr_finish_sequences */
+    int32_t groups_finished;  /* groups that left because their last member finished (not retired by the gate) */
 } sr_stats_t;
 
 /*
@@ -170,6 +175,22 @@ int sr_gate(sr_ctx *ctx, int turn, int32_t *out_sums, uint8_t *out_retire, void 
 int sr_retire_and_compact(sr_ctx *ctx, int *host_n_live_groups, void *stream);
 
 /*
+ * Take single sequences out of the batch because their trajectory has ended (success or failure
+ * reported by the environment) while other members of their group go on (Section 3.3 speaks of
+ * the members "still running").  host_done: HOST uint8 [n_live_seq], non-zero = finished.  Call
+ * between a turn's last sr_decode_step and the next sr_prefill_chunk: the sequence is recorded as
+ * finished after `turn` environment steps.  Its private KV pages are freed and its references to
+ * the shared prompt pages dropped; its action prefix is kept, because a later sr_gate still
+ * compares it with the other members' (a pair is then divided by the longer of the two prefix
+ * lengths, Section 3.2, and the member counts towards tau_K).  A group whose last member
+ * finishes leaves the batch without being retired.  Rows keep their order; the sync point is
+ * inside (page table and row maps are re-uploaded).  *host_n_live_seq (may be NULL) receives
+ * the number of sequences left.  SR_E_STATE: before the first turn or in the middle of one.
+ * After this call sr_gate writes to out_sums the plain sum of the pair distances.
+ */
+int sr_finish_sequences(sr_ctx *ctx, const uint8_t *host_done, int *host_n_live_seq, void *stream);
+
+/*
  * Stand-alone gate over many groups and several prefix lengths (no context needed).
  * actions: device int32 [n_groups][G][stride]; prefix_lens: HOST int [n_lens], each in
  * [1, min(stride, 32)]; sums: device int32 [n_lens][n_groups]; retire: device uint8
@@ -224,6 +245,8 @@ int sr_grpo_loss(const double *logprob, const float *rewards, int n_groups, int 
  *                  prefixes counts 0
  *   lev_scaled     the same sum before the division by C(G,2), exact, in units of
  *                  1 / lcm(1..32) = 1 / 144403552893600
+ *   lev_sum        the plain sum over pairs of the Levenshtein distances (S_K when nobody has
+ *                  finished early)
  *   bigram_jaccard mean over pairs of 1 - |A n B| / |A u B|, A and B the SETS of consecutive
  *                  action pairs of the two prefixes; two empty sets count as identical (0)
  *   unique_prefix  number of distinct prefixes among the G members (the ratio is this / G)
@@ -249,8 +272,9 @@ typedef struct {
     double bigram_jaccard;
     double action_entropy;
     int32_t unique_prefix, n_at_step, unique_action, unique_obs, n_done;
+    int32_t lev_sum;
     uint8_t cut_d, cut_or;
-    uint8_t reserved[2];
+    uint8_t reserved[6];
 } sr_signals_t;
 int sr_signals_batch(const int32_t *actions, const int32_t *obs, const int32_t *end_step, int n_groups, int G,
                      int stride, const int *prefix_lens, int n_lens, double d_L, double tau_H,

@@ -153,7 +153,7 @@ def gate_batch(actions, lens, d_L: float):
 
 SIGNALS_DTYPE = np.dtype([("d_K", "f8"), ("lev_scaled", "i8"), ("bigram_jaccard", "f8"), ("action_entropy", "f8"),
                           ("unique_prefix", "i4"), ("n_at_step", "i4"), ("unique_action", "i4"), ("unique_obs", "i4"),
-                          ("n_done", "i4"), ("cut_d", "u1"), ("cut_or", "u1")], align=True)
+                          ("n_done", "i4"), ("lev_sum", "i4"), ("cut_d", "u1"), ("cut_or", "u1")], align=True)
 
 
 def lcm32() -> int:
@@ -173,7 +173,7 @@ def signals_batch(actions, lens, d_L: float, tau_H: float = 2.0, obs=None, end_s
     o = _i32(obs) if obs is not None else None
     e = _i32(end_step) if end_step is not None else None
     out = np.zeros((len(lens), n_groups), dtype=SIGNALS_DTYPE)
-    assert SIGNALS_DTYPE.itemsize == 56
+    assert SIGNALS_DTYPE.itemsize == 64
     load().sro_signals_batch(a.ctypes.data, o.ctypes.data if o is not None else None,
                              e.ctypes.data if e is not None else None, n_groups, G, stride, lens.ctypes.data,
                              len(lens), d_L, tau_H, out.ctypes.data)
@@ -316,7 +316,8 @@ def grpo_loss(logprob_seq, rewards, G: int, eps: float = 1e-6):
 
 
 def run_episode(model: Model, prompts, obs_fn, G: int, turns: int, act_len: int, action_mod: int,
-                gate_turns, d_L: float, keep_logits: bool = False, temperature: float = 0.0, sample_seed: int = 0):
+                gate_turns, d_L: float, keep_logits: bool = False, temperature: float = 0.0, sample_seed: int = 0,
+                finish_fn=None, tau_H: float | None = None):
     """Rolls every group forward turn by turn, gating at the given turns.
 
     prompts: int32 [n_groups, P] (shared by the G members of a group).
@@ -326,6 +327,12 @@ def run_episode(model: Model, prompts, obs_fn, G: int, turns: int, act_len: int,
     turn's action id is (first decoded token) mod action_mod.  After a gate turn K the
     pairwise-distance sum S_K over the first K actions is compared with gate_bound and
     groups with S_K < bound stop there and leave the batch.
+
+    finish_fn(K, r) -> bool (optional): sequence r's trajectory ends after environment step K (reported by the
+    environment, i.e. an input here); it generates nothing further, its group goes on with the other members,
+    and a group whose last member ends leaves the batch without being cut.  With finish_fn the gate compares
+    prefixes of unequal length (each pair divided by the longer one) and, if tau_H is given, also cuts a group
+    when the fraction of its members that have ended is >= tau_H (Appendix E, Eq. 3).
 
     Returns a dict of per-turn records, all indexed by original sequence / group ids.
     """
@@ -337,7 +344,10 @@ def run_episode(model: Model, prompts, obs_fn, G: int, turns: int, act_len: int,
     seqs = [model.new_seq(cap) for _ in range(n_seq)]
     live = list(range(n_groups))
     actions = np.full((n_seq, turns), -1, dtype=np.int32)
-    rec = {"tokens": [], "gaps": [], "logits": [], "live_groups": [], "gate": {}, "decoded_tokens": 0}
+    alive = np.ones(n_seq, dtype=bool)
+    end_step = np.full(n_seq, 10 ** 6, dtype=np.int32)
+    rec = {"tokens": [], "gaps": [], "logits": [], "live_groups": [], "live_rows": [], "finished": [], "gate": {},
+           "decoded_tokens": 0}
 
     logits = [None] * n_seq
     for g in live:
@@ -346,8 +356,9 @@ def run_episode(model: Model, prompts, obs_fn, G: int, turns: int, act_len: int,
 
     for turn in range(turns):
         obs = obs0 if turn == 0 else obs_fn(turn)
-        rows = [g * G + m for g in live for m in range(G)]
+        rows = [g * G + m for g in live for m in range(G) if alive[g * G + m]]
         rec["live_groups"].append(list(live))
+        rec["live_rows"].append(list(rows))
         for r in rows:
             logits[r] = seqs[r].forward(obs[r])
         t_tok = np.full((act_len, n_seq), -1, dtype=np.int32)
@@ -370,12 +381,31 @@ def run_episode(model: Model, prompts, obs_fn, G: int, turns: int, act_len: int,
         rec["gaps"].append(t_gap)
         rec["logits"].append(t_log)
         K = turn + 1
+        done_now = [r for r in rows if finish_fn is not None and finish_fn(K, r)]
+        for r in done_now:
+            alive[r] = False
+            end_step[r] = K
+        rec["finished"].append(done_now)
+        live = [g for g in live if alive[g * G:(g + 1) * G].any()]
         if K in gate_turns:
-            bound = gate_bound(d_L, G, K)
-            sums = {g: pair_sum(actions[g * G:(g + 1) * G], K) for g in live}
-            cut = {g: sums[g] < bound for g in live}
-            rec["gate"][K] = {"bound": bound, "sums": sums, "cut": cut}
+            if finish_fn is None:
+                bound = gate_bound(d_L, G, K)
+                sums = {g: pair_sum(actions[g * G:(g + 1) * G], K) for g in live}
+                cut = {g: sums[g] < bound for g in live}
+                rec["gate"][K] = {"bound": bound, "sums": sums, "cut": cut}
+            elif live:
+                sig = signals_batch(np.stack([actions[g * G:(g + 1) * G] for g in live]), [K], d_L,
+                                    2.0 if tau_H is None else tau_H,
+                                    end_step=np.stack([end_step[g * G:(g + 1) * G] for g in live]))[0]
+                key = "cut_d" if tau_H is None else "cut_or"
+                rec["gate"][K] = {"sums": {g: int(sig["lev_sum"][i]) for i, g in enumerate(live)},
+                                  "cut": {g: bool(sig[key][i]) for i, g in enumerate(live)},
+                                  "n_done": {g: int(sig["n_done"][i]) for i, g in enumerate(live)}}
+            else:
+                rec["gate"][K] = {"sums": {}, "cut": {}, "n_done": {}}
+            cut = rec["gate"][K]["cut"]
             live = [g for g in live if not cut[g]]
     rec["actions"] = actions
+    rec["end_step"] = end_step
     rec["final_live_groups"] = live
     return rec

@@ -143,6 +143,7 @@ typedef struct {
     int32_t unique_action;    /* distinct a_{i,K} among them                                          */
     int32_t unique_obs;       /* distinct o_{i,K} among them                                          */
     int32_t n_done;           /* members that had finished by step K (end_step <= K)                  */
+    int32_t lev_sum;          /* plain sum over pairs of the edit distances                           */
     uint8_t cut_d;            /* Eq. 2: d_K < d_L                                                     */
     uint8_t cut_or;           /* Eq. 3: d_K < d_L or tau_K >= tau_H, tau_K = n_done / G               */
 } sro_signals_t;
@@ -173,12 +174,14 @@ void sro_signals(const int32_t *actions, const int32_t *obs, const int32_t *end_
     /* mean pairwise prefix edit distance, and the action-bigram Jaccard distance */
     double dsum = 0.0, jsum = 0.0;
     int64_t scaled = 0;
+    int32_t plain = 0;
     for (int i = 0; i < G; ++i)
         for (int j = i + 1; j < G; ++j) {
             const int32_t *a = actions + (size_t)i * stride, *b = actions + (size_t)j * stride;
             const int longer = len[i] > len[j] ? len[i] : len[j];
             if (longer > 0) {
                 const int d = sro_lev(a, len[i], b, len[j]);
+                plain += d;
                 dsum += (double)d / (double)longer;
                 scaled += (int64_t)d * (SRO_LCM32 / longer);
             }
@@ -193,6 +196,7 @@ void sro_signals(const int32_t *actions, const int32_t *obs, const int32_t *end_
         }
     out->d_K = dsum / (double)P;
     out->lev_scaled = scaled;
+    out->lev_sum = plain;
     out->bigram_jaccard = jsum / (double)P;
 
     /* distinct prefixes */

@@ -18,7 +18,7 @@ SR_OK, SR_E_ARG, SR_E_NOMEM, SR_E_STATE, SR_E_HIP = 0, -1, -2, -3, -4
 EXPORTS = ("sr_init", "sr_destroy", "sr_load_weights", "sr_prefill_chunk", "sr_decode_step", "sr_gate",
            "sr_retire_and_compact", "sr_gate_batch", "sr_set_actions", "sr_get_actions", "sr_get_logits",
            "sr_get_live_map", "sr_stats", "sr_strerror", "sr_profile", "sr_profile_read", "sr_signals_batch",
-           "sr_score_chunk", "sr_get_logprob", "sr_grpo_loss")
+           "sr_score_chunk", "sr_get_logprob", "sr_grpo_loss", "sr_finish_sequences")
 
 KERNEL_CLASSES = ("norm", "gemm_qkv", "qkv_post", "attn_decode", "attn_prefill", "attn_merge",
                   "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm_head", "argmax")
@@ -41,7 +41,7 @@ class Options(ctypes.Structure):
     _fields_ = [("page_tokens", ctypes.c_int32), ("max_seq_len", ctypes.c_int32), ("max_turns", ctypes.c_int32),
                 ("action_mod", ctypes.c_int32), ("max_prefill_rows", ctypes.c_int32),
                 ("kv_pool_bytes", ctypes.c_uint64), ("temperature", ctypes.c_float),
-                ("sample_seed", ctypes.c_uint64)]
+                ("sample_seed", ctypes.c_uint64), ("tau_H", ctypes.c_float)]
 
 
 class LayerWeights(ctypes.Structure):
@@ -61,7 +61,8 @@ class KernelTime(ctypes.Structure):
 class Stats(ctypes.Structure):
     _fields_ = [("decoded_tokens", ctypes.c_int64), ("prefill_tokens", ctypes.c_int64)] + \
                [(n, ctypes.c_int32) for n in ("n_live_groups", "n_live_seq", "seq_len", "turn", "pages_total",
-                                              "pages_in_use", "groups_retired", "pages_freed", "cow_page_copies")]
+                                              "pages_in_use", "groups_retired", "pages_freed", "cow_page_copies",
+                                              "seqs_finished", "groups_finished")]
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}
@@ -90,6 +91,7 @@ def lib():
         L.sr_score_chunk.argtypes = [vp, vp, vp, ci, vp, vp]
         L.sr_get_logprob.argtypes = [vp, vp, vp]
         L.sr_grpo_loss.argtypes = [vp, vp, ci, ci, ctypes.c_double, vp, vp, vp, vp]
+        L.sr_finish_sequences.argtypes = [vp, vp, ctypes.POINTER(ci), vp]
         L.sr_set_actions.argtypes = [vp, ci, vp, vp]
         L.sr_get_actions.argtypes = [vp, vp, vp]
         L.sr_get_logits.argtypes = [vp, vp, vp]
@@ -139,10 +141,10 @@ def sr_gate_batch(actions, prefix_lens, threshold: float, sums=None, retire=None
                                _ptr(sums), _ptr(retire), _stream(stream)), "sr_gate_batch")
 
 
-SIGNALS_BYTES = 56       # sizeof(sr_signals_t)
+SIGNALS_BYTES = 64       # sizeof(sr_signals_t)
 SIGNALS_FIELDS = (("d_K", "f8"), ("lev_scaled", "i8"), ("bigram_jaccard", "f8"), ("action_entropy", "f8"),
                   ("unique_prefix", "i4"), ("n_at_step", "i4"), ("unique_action", "i4"), ("unique_obs", "i4"),
-                  ("n_done", "i4"), ("cut_d", "u1"), ("cut_or", "u1"), ("reserved", "u1", (2,)))
+                  ("n_done", "i4"), ("lev_sum", "i4"), ("cut_d", "u1"), ("cut_or", "u1"), ("reserved", "u1", (6,)))
 
 
 def sr_signals_batch(actions, prefix_lens, d_L: float, tau_H: float, out, obs=None, end_step=None, stream=None):
@@ -167,11 +169,11 @@ class Context:
 
     def __init__(self, shape, n_groups: int, G: int, threshold: float, *, page_tokens=64, max_seq_len=4096,
                  max_turns=32, action_mod=64, max_prefill_rows=0, kv_pool_bytes=1 << 30, temperature=0.0,
-                 sample_seed=0):
+                 sample_seed=0, tau_H=0.0):
         self.shape = ModelShape(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
                                 shape.ffn, shape.vocab, shape.rms_eps, shape.rope_theta, int(shape.qkv_bias))
         self.opt = Options(page_tokens, max_seq_len, max_turns, action_mod, max_prefill_rows, kv_pool_bytes,
-                           temperature, sample_seed)
+                           temperature, sample_seed, tau_H)
         self.G, self.n_groups0, self.vocab, self.max_turns = G, n_groups, shape.vocab, max_turns
         self._h = ctypes.c_void_p()
         _check(lib().sr_init(ctypes.byref(self._h), ctypes.byref(self.shape), n_groups, G, threshold,
@@ -213,6 +215,15 @@ class Context:
 
     def sr_gate(self, turn: int, out_sums=None, out_retire=None, stream=None):
         _check(lib().sr_gate(self._h, turn, _ptr(out_sums), _ptr(out_retire), _stream(stream)), "sr_gate")
+
+    def sr_finish_sequences(self, host_done, stream=None) -> int:
+        """host_done: numpy uint8 [n_live_seq]; returns the number of sequences left."""
+        import numpy as np
+        d = np.ascontiguousarray(host_done, dtype=np.uint8)
+        n = ctypes.c_int(-1)
+        _check(lib().sr_finish_sequences(self._h, d.ctypes.data, ctypes.byref(n), _stream(stream)),
+               "sr_finish_sequences")
+        return n.value
 
     def sr_retire_and_compact(self, stream=None) -> int:
         n = ctypes.c_int(-1)

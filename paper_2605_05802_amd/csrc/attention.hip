@@ -48,7 +48,9 @@ __global__ __launch_bounds__(256, RT == 1 ? 3 : 2) void attn_kernel(AttnArgs a, 
     const int n_rep = a.n_q / a.n_kv;
 
     const int c = lane & 15, g = lane >> 4;
-    const int32_t *pt = a.page_table + (size_t)unit * p.pt_row_stride * a.pt_stride;
+    const int u_row0 = p.unit_row0 ? p.unit_row0[unit] : unit * p.q_per_unit;   // first query token of the unit
+    const int u_count = p.unit_count ? p.unit_count[unit] : p.q_per_unit;       // its query tokens
+    const int32_t *pt = a.page_table + (size_t)(p.unit_row0 ? u_row0 : unit * p.pt_row_stride) * a.pt_stride;
     const int blocks_per_page = a.page_tokens >> 5;
     const size_t block_elems = (size_t)32 * D;
     auto block_base = [&](int t0) -> size_t {
@@ -66,9 +68,9 @@ __global__ __launch_bounds__(256, RT == 1 ? 3 : 2) void attn_kernel(AttnArgs a, 
         const int row = rt * 16 + c;
         const int qi = qtile * p.q_per_item + row / n_rep;       // query token within the unit
         const int hr = row % n_rep;
-        const bool used = (row < p.q_per_item * n_rep) && (qi < p.q_per_unit);
+        const bool used = (row < p.q_per_item * n_rep) && (qi < u_count);
         limit[rt] = used ? p.causal_pos0 + qi * p.causal_stride : -1;
-        const size_t qtok = (size_t)unit * p.q_per_unit + qi;
+        const size_t qtok = (size_t)u_row0 + qi;
         const uint16_t *qp = a.q + (qtok * a.n_q + kvh * n_rep + hr) * D + 8 * g;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
@@ -256,7 +258,8 @@ __global__ __launch_bounds__(128) void attn_merge_kernel(MergeArgs a) {
     int n_items = 0;
     for (int ph = 0; ph < a.n_phases; ++ph) {
         const AttnPhase &p = a.ph[ph];
-        const int unit = qt / p.q_per_unit, qi = qt % p.q_per_unit;
+        const int unit = p.row_unit ? p.row_unit[qt] : qt / p.q_per_unit;
+        const int qi = p.row_unit ? qt - p.unit_row0[unit] : qt % p.q_per_unit;
         const int qtile = qi / p.q_per_item, row = (qi % p.q_per_item) * n_rep + hr;
         const size_t item0 = ((size_t)unit * a.n_kv + kvh) * p.n_splits;
         if (dd < p.n_splits) {

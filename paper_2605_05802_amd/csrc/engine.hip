@@ -3,6 +3,7 @@
 // The host owns the page allocator: every live sequence advances in lock step, so the pages a
 // call needs are known before anything is launched, and only the retire mask (one byte per
 // group, once per gate turn) ever flows from the device to the host.
+#include <limits.h>
 #include <math.h>
 #include <string.h>
 
@@ -69,6 +70,22 @@ struct sr_ctx {
     uint8_t *h_retire = nullptr;                // pinned [n_groups0]
     int32_t *h_rows = nullptr;                  // pinned [n_seq0]
 
+    // groups some of whose members have finished (sr_finish_sequences)
+    int n_rows = 0;                            // live sequences = rows of every per-sequence array
+    std::vector<int> grp_count;                // live members of every live group (rows are group-major)
+    std::vector<int> row_orig;                 // original sequence id of every live row (host mirror of d_orig)
+    std::vector<int> end_step;                 // by ORIGINAL sequence id: turn after which it finished, or INT_MAX
+    std::vector<int> fin_index;                // by original id: row of its saved actions in d_fin_actions, or -1
+    int n_finished = 0;
+    bool irregular = false;                    // some live group has fewer than G live members
+    int32_t *h_units = nullptr;                // pinned [2 * n_groups0 + n_seq0]: unit_row0, unit_count, row_unit
+    int32_t *d_units = nullptr;                // device copy
+    int32_t *h_gate_map = nullptr;             // pinned [2 * n_seq0]: source of every gate slot, its end step
+    int32_t *d_gate_map = nullptr;
+    int32_t *d_fin_actions = nullptr;          // [n_seq0][max_turns]: action rows of finished members, in finishing order
+    int32_t *d_gate_actions = nullptr;         // [n_groups0][G][max_turns]: gate input assembled from live and finished rows
+    sr_signals_t *d_gate_sig = nullptr;        // [n_groups0]
+
     // device batch state
     int32_t *d_pt = nullptr;
     int32_t *d_actions[2] = {nullptr, nullptr};
@@ -99,7 +116,7 @@ struct sr_ctx {
     std::vector<ProfRec> prof;
     std::vector<hipEvent_t> event_pool;
 
-    int n_live_seq() const { return n_live_groups * G; }
+    int n_live_seq() const { return n_rows; }
 };
 
 namespace {
@@ -216,6 +233,7 @@ void drop_page(sr_ctx *c, int p, int *freed) {
 // append into a page that other members still reference gets its own copy first.
 int grow_pages(sr_ctx *c, int new_len, bool shared, hipStream_t st) {
     const int pt = c->o.page_tokens, G = c->G;
+    if (shared && c->irregular) return SR_E_STATE;      // a shared chunk needs every group complete
     const int need = ceil_div(new_len, pt);
     const int n_seq = c->n_live_seq();
     // count first, so that a failure launches nothing and changes nothing
@@ -253,6 +271,41 @@ int grow_pages(sr_ctx *c, int new_len, bool shared, hipStream_t st) {
         }
     }
     return upload_page_table(c, st);
+}
+
+// Row ranges of the live groups, for the kernels that walk a group's members (decode attention over the
+// shared prompt) once groups have become unequal.
+int upload_units(sr_ctx *c, hipStream_t st) {
+    c->irregular = false;
+    int row = 0;
+    int32_t *row0 = c->h_units, *cnt = c->h_units + c->n_groups0, *ru = c->h_units + 2 * c->n_groups0;
+    for (int g = 0; g < c->n_live_groups; ++g) {
+        row0[g] = row;
+        cnt[g] = c->grp_count[g];
+        for (int m = 0; m < c->grp_count[g]; ++m) ru[row + m] = g;
+        row += c->grp_count[g];
+        if (c->grp_count[g] != c->G) c->irregular = true;
+    }
+    if (c->irregular) {
+        SR_HIP(hipMemcpyAsync(c->d_units, c->h_units, (size_t)(2 * c->n_groups0 + c->n_seq0) * 4,
+                              hipMemcpyHostToDevice, st));
+        SR_HIP(hipStreamSynchronize(st));     // the staging buffer may be rewritten by the next call
+    }
+    return SR_OK;
+}
+
+// Keep the rows listed in h_rows[0 .. n) of every per-sequence device array, in that order.
+int compact_rows(sr_ctx *c, int n, hipStream_t st) {
+    if (n <= 0) return SR_OK;
+    SR_HIP(hipMemcpyAsync(c->d_rows, c->h_rows, (size_t)n * 4, hipMemcpyHostToDevice, st));
+    const int nxt = c->cur ^ 1;
+    SR_TRY(launch_gather_rows(c->d_actions[nxt], c->d_actions[c->cur], c->d_rows, n, (size_t)c->o.max_turns * 4, st));
+    SR_TRY(launch_gather_rows(c->d_logits[nxt], c->d_logits[c->cur], c->d_rows, n, (size_t)c->s.vocab * 4, st));
+    SR_TRY(launch_gather_rows(c->d_orig[nxt], c->d_orig[c->cur], c->d_rows, n, 4, st));
+    SR_TRY(launch_gather_rows(c->d_logprob[nxt], c->d_logprob[c->cur], c->d_rows, n, 8, st));
+    c->cur = nxt;
+    SR_HIP(hipStreamSynchronize(st));         // h_rows may be rewritten by the next compaction
+    return SR_OK;
 }
 
 struct Pass {
@@ -330,8 +383,13 @@ int forward(sr_ctx *c, const Pass &p, hipStream_t st) {
     if (p.decode) {
         if (c->shared_tokens > 0) {
             AttnPhase x{};
-            x.n_units = p.n_units / c->G;
+            x.n_units = c->n_live_groups;
             x.q_per_unit = c->G;
+            if (c->irregular) {                     // groups of unequal size: the kernels take the row ranges from maps
+                x.unit_row0 = c->d_units;
+                x.unit_count = c->d_units + c->n_groups0;
+                x.row_unit = c->d_units + 2 * c->n_groups0;
+            }
             x.rt = n_rep > 16 ? 2 : 1;              // same row-tile count as the private phase: one launch
             x.q_per_item = (16 * x.rt) / n_rep < c->G ? (16 * x.rt) / n_rep : c->G;
             x.items_per_unit = ceil_div(c->G, x.q_per_item);
@@ -551,6 +609,8 @@ void sr_destroy(sr_ctx *c) {
     if (c->h_pt) (void)hipHostFree(c->h_pt);
     if (c->h_retire) (void)hipHostFree(c->h_retire);
     if (c->h_rows) (void)hipHostFree(c->h_rows);
+    if (c->h_units) (void)hipHostFree(c->h_units);
+    if (c->h_gate_map) (void)hipHostFree(c->h_gate_map);
     for (auto &r : c->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
     for (hipEvent_t e : c->event_pool) (void)hipEventDestroy(e);
     delete c;
@@ -607,6 +667,19 @@ static int init_impl(sr_ctx *c) {
     c->n_live_groups = c->n_groups0;
     c->live_orig_group.resize(c->n_groups0);
     for (int g = 0; g < c->n_groups0; ++g) c->live_orig_group[g] = g;
+    c->n_rows = c->n_seq0;
+    c->grp_count.assign(c->n_groups0, c->G);
+    c->row_orig.resize(c->n_seq0);
+    for (int r = 0; r < c->n_seq0; ++r) c->row_orig[r] = r;
+    c->end_step.assign(c->n_seq0, INT_MAX);
+    c->fin_index.assign(c->n_seq0, -1);
+    SR_HIP(hipHostMalloc((void **)&c->h_units, (size_t)(2 * c->n_groups0 + c->n_seq0) * 4 + 16, hipHostMallocDefault));
+    SR_HIP(hipHostMalloc((void **)&c->h_gate_map, (size_t)2 * c->n_seq0 * 4 + 16, hipHostMallocDefault));
+    SR_TRY(dev_alloc(c, &c->d_units, (size_t)2 * c->n_groups0 + c->n_seq0));
+    SR_TRY(dev_alloc(c, &c->d_gate_map, (size_t)2 * c->n_seq0));
+    SR_TRY(dev_alloc(c, &c->d_fin_actions, (size_t)c->n_seq0 * o.max_turns));
+    SR_TRY(dev_alloc(c, &c->d_gate_actions, (size_t)c->n_seq0 * o.max_turns));
+    SR_TRY(dev_alloc(c, &c->d_gate_sig, (size_t)c->n_groups0));
     c->pages.assign(c->n_seq0, {});
     SR_HIP(hipHostMalloc((void **)&c->h_pt, (size_t)c->n_seq0 * c->max_pages * 4 + 16, hipHostMallocDefault));
     SR_HIP(hipHostMalloc((void **)&c->h_retire, c->n_groups0 + 16, hipHostMallocDefault));
@@ -668,7 +741,7 @@ int sr_init(sr_ctx **out, const sr_model_shape *shape, int n_groups, int G, doub
         return SR_E_ARG;
     if ((opt->page_tokens != 32 && opt->page_tokens != 64 && opt->page_tokens != 128) || opt->max_seq_len < 1 ||
         opt->max_turns < 1 || opt->max_turns > 32 || opt->action_mod < 0 || opt->max_prefill_rows < 0 ||
-        !(opt->temperature >= 0.f))
+        !(opt->temperature >= 0.f) || !(opt->tau_H >= 0.f) || opt->tau_H > 4.f)
         return SR_E_ARG;
     sr_ctx *c = new sr_ctx();
     c->s = s;
@@ -896,15 +969,86 @@ int sr_gate(sr_ctx *c, int turn, int32_t *out_sums, uint8_t *out_retire, void *s
     if (!c || turn < 1 || turn > c->o.max_turns) return SR_E_ARG;
     if (c->actions_recorded < turn) return SR_E_STATE;
     hipStream_t st = (hipStream_t)stream;
-    GateLens lens{};
-    lens.n = 1;
-    lens.len[0] = turn;
-    lens.bound[0] = (int)gate_bound(c->threshold, c->G, turn);
-    const int ng = c->n_live_groups;
-    SR_TRY(launch_gate(c->d_actions[c->cur], ng, c->G, c->o.max_turns, lens, c->d_sums, c->d_retire, st));
+    const int ng = c->n_live_groups, G = c->G, T = c->o.max_turns;
+    if (c->n_finished == 0) {
+        // every member of every live group holds exactly `turn` actions: the equal-length form of Eq. 2
+        GateLens lens{};
+        lens.n = 1;
+        lens.len[0] = turn;
+        lens.bound[0] = (int)gate_bound(c->threshold, G, turn);
+        SR_TRY(launch_gate(c->d_actions[c->cur], ng, G, T, lens, c->d_sums, c->d_retire, st));
+    } else if (ng > 0) {
+        // some members finished early: gather each group's G action rows (live rows and saved rows of
+        // finished members, in member order) and evaluate d_K with per-pair longer-length normalisation,
+        // and the termination-fraction clause when tau_H is set
+        int32_t *src = c->h_gate_map, *end = c->h_gate_map + c->n_seq0;
+        int row = 0;
+        for (int g = 0; g < ng; ++g) {
+            const int og = c->live_orig_group[g];
+            for (int m = 0; m < G; ++m) {
+                const int orig = og * G + m;
+                if (c->end_step[orig] == INT_MAX) {
+                    src[g * G + m] = row++;
+                    end[g * G + m] = INT_MAX;
+                } else {
+                    src[g * G + m] = -1 - c->fin_index[orig];
+                    end[g * G + m] = c->end_step[orig];
+                }
+            }
+        }
+        SR_HIP(hipMemcpyAsync(c->d_gate_map, c->h_gate_map, (size_t)2 * c->n_seq0 * 4, hipMemcpyHostToDevice, st));
+        SR_HIP(hipStreamSynchronize(st));     // the staging buffer may be rewritten by the next gate
+        SR_TRY(launch_assemble_gate(c->d_gate_map, c->d_actions[c->cur], c->d_fin_actions, ng * G, T,
+                                    c->d_gate_actions, st));
+        const int len1 = turn;
+        const double tau = c->o.tau_H > 0.f ? (double)c->o.tau_H : 2.0;
+        SR_TRY(sr_signals_batch(c->d_gate_actions, nullptr, c->d_gate_map + c->n_seq0, ng, G, T, &len1, 1,
+                                c->threshold, tau, c->d_gate_sig, st));
+        SR_TRY(launch_extract_gate(c->d_gate_sig, ng, c->o.tau_H > 0.f ? 1 : 0, c->d_sums, c->d_retire, st));
+    }
     if (ng > 0 && out_sums) SR_HIP(hipMemcpyAsync(out_sums, c->d_sums, (size_t)ng * 4, hipMemcpyDeviceToDevice, st));
-    if (ng > 0 && out_retire) SR_HIP(hipMemcpyAsync(out_retire, c->d_retire, (size_t)ng, hipMemcpyDeviceToDevice, st));
+    if (ng > 0 && out_retire) SR_HIP(hipMemcpyAsync(out_retire, c->d_retire, ng, hipMemcpyDeviceToDevice, st));
     c->gate_pending = true;
+    return SR_OK;
+}
+
+// Drop the live rows for which drop[row] is set (their pages go back to the pool), keep the others in order,
+// and drop the groups left without a live member.
+static int remove_rows(sr_ctx *c, const std::vector<char> &drop, int *freed, hipStream_t st) {
+    const int ng = c->n_live_groups, n = c->n_rows;
+    int kept_rows = 0, kept_groups = 0, row = 0;
+    for (int g = 0; g < ng; ++g) {
+        int alive = 0;
+        for (int m = 0; m < c->grp_count[g]; ++m, ++row) {
+            if (drop[row]) {
+                for (int pg : c->pages[row]) drop_page(c, pg, freed);
+                c->pages[row].clear();
+                continue;
+            }
+            if (kept_rows != row) {
+                c->pages[kept_rows] = std::move(c->pages[row]);
+                c->pages[row].clear();
+                c->row_orig[kept_rows] = c->row_orig[row];
+            }
+            c->h_rows[kept_rows++] = row;
+            ++alive;
+        }
+        if (alive > 0) {
+            c->live_orig_group[kept_groups] = c->live_orig_group[g];
+            c->grp_count[kept_groups++] = alive;
+        }
+    }
+    if (kept_rows != n) {
+        c->live_orig_group.resize(kept_groups);
+        c->grp_count.resize(kept_groups);
+        c->row_orig.resize(kept_rows);
+        SR_TRY(compact_rows(c, kept_rows, st));
+        c->n_live_groups = kept_groups;
+        c->n_rows = kept_rows;
+        SR_TRY(upload_units(c, st));
+        c->pt_dirty = true;
+        SR_TRY(upload_page_table(c, st));
+    }
     return SR_OK;
 }
 
@@ -913,7 +1057,7 @@ int sr_retire_and_compact(sr_ctx *c, int *host_n_live_groups, void *stream) {
     if (!c->gate_pending) return SR_E_STATE;
     hipStream_t st = (hipStream_t)stream;
     c->gate_pending = false;
-    const int ng = c->n_live_groups, G = c->G;
+    const int ng = c->n_live_groups;
     if (ng == 0) {
         if (host_n_live_groups) *host_n_live_groups = 0;
         return SR_OK;
@@ -921,43 +1065,48 @@ int sr_retire_and_compact(sr_ctx *c, int *host_n_live_groups, void *stream) {
     SR_HIP(hipMemcpyAsync(c->h_retire, c->d_retire, ng, hipMemcpyDeviceToHost, st));
     SR_HIP(hipStreamSynchronize(st));
 
-    int kept = 0, freed = 0;
+    std::vector<char> drop(c->n_rows, 0);
+    int row = 0, freed = 0;
     for (int g = 0; g < ng; ++g) {
-        if (c->h_retire[g]) {
-            for (int m = 0; m < G; ++m)
-                for (int pg : c->pages[g * G + m]) drop_page(c, pg, &freed);
-            c->st.groups_retired++;
-        } else {
-            if (kept != g) {
-                c->live_orig_group[kept] = c->live_orig_group[g];
-                for (int m = 0; m < G; ++m) c->pages[kept * G + m] = std::move(c->pages[g * G + m]);
-            }
-            for (int m = 0; m < G; ++m) c->h_rows[kept * G + m] = g * G + m;
-            ++kept;
-        }
+        if (c->h_retire[g]) c->st.groups_retired++;
+        for (int m = 0; m < c->grp_count[g]; ++m, ++row) drop[row] = c->h_retire[g] ? 1 : 0;
     }
+    SR_TRY(remove_rows(c, drop, &freed, st));
     c->st.pages_freed += freed;
-    if (kept != ng) {
-        for (int r = kept * G; r < ng * G; ++r) c->pages[r].clear();
-        c->live_orig_group.resize(kept);
-        const int n = kept * G;
-        if (n > 0) {
-            // move the surviving rows of every per-sequence device array, keeping their order
-            SR_HIP(hipMemcpyAsync(c->d_rows, c->h_rows, (size_t)n * 4, hipMemcpyHostToDevice, st));
-            const int nxt = c->cur ^ 1;
-            SR_TRY(launch_gather_rows(c->d_actions[nxt], c->d_actions[c->cur], c->d_rows, n,
-                                      (size_t)c->o.max_turns * 4, st));
-            SR_TRY(launch_gather_rows(c->d_logits[nxt], c->d_logits[c->cur], c->d_rows, n, (size_t)c->s.vocab * 4, st));
-            SR_TRY(launch_gather_rows(c->d_orig[nxt], c->d_orig[c->cur], c->d_rows, n, 4, st));
-            SR_TRY(launch_gather_rows(c->d_logprob[nxt], c->d_logprob[c->cur], c->d_rows, n, 8, st));
-            c->cur = nxt;
-            SR_HIP(hipStreamSynchronize(st));     // h_rows may be rewritten by the next compaction
+    if (host_n_live_groups) *host_n_live_groups = c->n_live_groups;
+    return SR_OK;
+}
+
+int sr_finish_sequences(sr_ctx *c, const uint8_t *host_done, int *host_n_live_seq, void *stream) {
+    if (!c || !host_done) return SR_E_ARG;
+    if (c->turn < 1 || c->first_decode_of_turn) return SR_E_STATE;    // between a turn's decode and the next prefill
+    hipStream_t st = (hipStream_t)stream;
+    const int n = c->n_rows;
+    std::vector<char> drop(n, 0);
+    int n_done = 0;
+    for (int r = 0; r < n; ++r)
+        if (host_done[r]) {
+            drop[r] = 1;
+            c->h_rows[n_done++] = r;
         }
-        c->n_live_groups = kept;
-        c->pt_dirty = true;
-        SR_TRY(upload_page_table(c, st));
+    if (n_done > 0) {
+        // keep the finished members' action rows: the gate of a later turn still compares their prefixes
+        SR_HIP(hipMemcpyAsync(c->d_rows, c->h_rows, (size_t)n_done * 4, hipMemcpyHostToDevice, st));
+        SR_TRY(launch_gather_rows(c->d_fin_actions + (size_t)c->n_finished * c->o.max_turns, c->d_actions[c->cur],
+                                  c->d_rows, n_done, (size_t)c->o.max_turns * 4, st));
+        SR_HIP(hipStreamSynchronize(st));
+        for (int i = 0; i < n_done; ++i) {
+            const int orig = c->row_orig[c->h_rows[i]];
+            c->end_step[orig] = c->turn;
+            c->fin_index[orig] = c->n_finished++;
+        }
+        const int groups_before = c->n_live_groups;
+        int freed = 0;
+        SR_TRY(remove_rows(c, drop, &freed, st));
+        c->st.seqs_finished += n_done;
+        c->st.groups_finished += groups_before - c->n_live_groups;
     }
-    if (host_n_live_groups) *host_n_live_groups = kept;
+    if (host_n_live_seq) *host_n_live_seq = c->n_rows;
     return SR_OK;
 }
 
@@ -992,8 +1141,7 @@ int sr_get_logits(sr_ctx *c, float *dst, void *stream) {
 
 int sr_get_live_map(sr_ctx *c, int32_t *host_orig_seq_ids) {
     if (!c || !host_orig_seq_ids) return SR_E_ARG;
-    for (int g = 0; g < c->n_live_groups; ++g)
-        for (int m = 0; m < c->G; ++m) host_orig_seq_ids[g * c->G + m] = c->live_orig_group[g] * c->G + m;
+    for (int r = 0; r < c->n_rows; ++r) host_orig_seq_ids[r] = c->row_orig[r];
     return SR_OK;
 }
 

@@ -21,7 +21,7 @@
 // floating-point results do not depend on scheduling.
 #include "sr_internal.h"
 
-static_assert(sizeof(sr_signals_t) == 56, "sr_signals_t is part of the C boundary");
+static_assert(sizeof(sr_signals_t) == 64, "sr_signals_t is part of the C boundary");
 
 namespace sr {
 namespace {
@@ -163,8 +163,10 @@ __global__ __launch_bounds__(kSigThreads) void signals_kernel(
         const PairRec *pr = &s_pair[l][g * pairs];
         double dsum = 0.0, jsum = 0.0;
         long long scaled = 0;
+        int lev_sum = 0;
         for (int q = 0; q < pairs; ++q) {
             const PairRec r = pr[q];
+            lev_sum += r.lev;
             if (r.longer > 0) {
                 dsum += (double)r.lev / (double)r.longer;
                 scaled += (long long)r.lev * (kLcm32 / r.longer);
@@ -215,14 +217,52 @@ __global__ __launch_bounds__(kSigThreads) void signals_kernel(
         o.unique_action = ua;
         o.unique_obs = obs ? uo : 0;
         o.n_done = n_done;
+        o.lev_sum = lev_sum;
         o.cut_d = (uint8_t)(scaled < lens.d_bound);
         o.cut_or = (uint8_t)(o.cut_d || (long long)n_done * 1000000LL >= lens.tau_num * G);
-        o.reserved[0] = o.reserved[1] = 0;
+        for (int i = 0; i < 6; ++i) o.reserved[i] = 0;
         out[(size_t)l * n_groups + g0 + g] = o;
     }
 }
 
+__global__ void assemble_gate_kernel(const int32_t *__restrict__ src, const int32_t *__restrict__ live_actions,
+                                     const int32_t *__restrict__ fin_actions, int n_slots, int max_turns,
+                                     int32_t *__restrict__ out) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_slots * max_turns) return;
+    const int s = i / max_turns, t = i - s * max_turns;
+    const int r = src[s];
+    out[i] = r >= 0 ? live_actions[(size_t)r * max_turns + t] : fin_actions[(size_t)(-1 - r) * max_turns + t];
+}
+
+__global__ void extract_gate_kernel(const sr_signals_t *__restrict__ sig, int n_groups, int use_or,
+                                    int32_t *__restrict__ sums, uint8_t *__restrict__ retire) {
+    const int g = blockIdx.x * blockDim.x + threadIdx.x;
+    if (g >= n_groups) return;
+    sums[g] = sig[g].lev_sum;
+    retire[g] = use_or ? sig[g].cut_or : sig[g].cut_d;
+}
+
 }  // namespace
+
+int launch_assemble_gate(const int32_t *src, const int32_t *live_actions, const int32_t *fin_actions, int n_slots,
+                         int max_turns, int32_t *out, hipStream_t stream) {
+    const int n = n_slots * max_turns;
+    if (n <= 0) return SR_OK;
+    assemble_gate_kernel<<<dim3((n + 255) / 256), dim3(256), 0, stream>>>(src, live_actions, fin_actions, n_slots,
+                                                                         max_turns, out);
+    SR_HIP(hipGetLastError());
+    return SR_OK;
+}
+
+int launch_extract_gate(const sr_signals_t *sig, int n_groups, int use_or, int32_t *sums, uint8_t *retire,
+                        hipStream_t stream) {
+    if (n_groups <= 0) return SR_OK;
+    extract_gate_kernel<<<dim3((n_groups + 255) / 256), dim3(256), 0, stream>>>(sig, n_groups, use_or, sums, retire);
+    SR_HIP(hipGetLastError());
+    return SR_OK;
+}
+
 }  // namespace sr
 
 extern "C" int sr_signals_batch(const int32_t *actions, const int32_t *obs, const int32_t *end_step, int n_groups,

@@ -78,6 +78,14 @@ struct GateLens {
 int launch_gate(const int32_t *actions, int n_groups, int G, int stride, const GateLens &lens,
                 int32_t *sums, uint8_t *retire, hipStream_t stream);
 
+// Gate input of groups with finished members: slot s (group-major, G per group) takes the action row
+// src[s] of live_actions when src[s] >= 0, else row -1 - src[s] of fin_actions.
+int launch_assemble_gate(const int32_t *src, const int32_t *live_actions, const int32_t *fin_actions, int n_slots,
+                         int max_turns, int32_t *out, hipStream_t stream);
+// sums[g] = sig[g].lev_sum; retire[g] = use_or ? sig[g].cut_or : sig[g].cut_d
+int launch_extract_gate(const sr_signals_t *sig, int n_groups, int use_or, int32_t *sums, uint8_t *retire,
+                        hipStream_t stream);
+
 // ---------------------------------------------------------------------------------------------
 // weights
 // ---------------------------------------------------------------------------------------------
@@ -187,6 +195,11 @@ struct AttnPhase {
     int causal_pos0, causal_stride;  // query token i of a unit sees tokens t <= causal_pos0 + i*causal_stride
     int n_splits, split_tokens;      // split s covers [t_begin + s*split_tokens, ...) (multiples of 32)
     int rt;              // row tiles per item (1 or 2)
+    // Units of unequal size (a group some of whose members have left the batch): unit u owns query tokens
+    // unit_row0[u] .. unit_row0[u] + unit_count[u] - 1 (count <= q_per_unit) and its pages are those of row
+    // unit_row0[u]; row_unit[token] is the unit of a query token.  All three null: unit u owns tokens
+    // u * q_per_unit .. and page-table row u * pt_row_stride.
+    const int32_t *unit_row0, *unit_count, *row_unit;
     float *part_o;       // [items][16*rt][d] fp32 un-normalised outputs
     float *part_ml;      // [items][16*rt][2] running max (scaled logits) and sum
 };

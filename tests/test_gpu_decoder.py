@@ -25,19 +25,19 @@ def dev(a):
 
 
 def run_and_compare(shape, cfg, seed, *, page_tokens=32, max_prefill_rows=0, sigma=0.02, weights=None,
-                    kv_pool_bytes=1 << 28):
+                    kv_pool_bytes=1 << 28, finish_fn=None, tau_H=None):
     """Runs the whole gated episode on both sides; returns (rec, stats, worst logit error, token mismatches)."""
     w = weights if weights is not None else synth.make_weights(shape, seed=0, sigma=sigma)
     conv = synth.converging_groups(cfg, seed)
     prompts = synth.prompts(cfg, shape.vocab, seed)
     obs_fn = lambda t: synth.observations(cfg, shape.vocab, seed, t, conv)
     rec = oracle.run_episode(oracle.Model(w), prompts, obs_fn, cfg.G, cfg.turns, cfg.act_len, cfg.action_mod,
-                             cfg.gate_turns, cfg.threshold, keep_logits=True)
+                             cfg.gate_turns, cfg.threshold, keep_logits=True, finish_fn=finish_fn, tau_H=tau_H)
 
     max_len = cfg.prompt_len + cfg.turns * (cfg.obs_len + cfg.act_len)
     ctx = sr.Context(shape, cfg.n_groups, cfg.G, cfg.threshold, page_tokens=page_tokens, max_seq_len=max_len,
                      max_turns=max(cfg.turns, 1), action_mod=cfg.action_mod, max_prefill_rows=max_prefill_rows,
-                     kv_pool_bytes=kv_pool_bytes)
+                     kv_pool_bytes=kv_pool_bytes, tau_H=tau_H or 0.0)
     load_host_weights(ctx, w)
     ctx.sr_prefill_chunk(dev(prompts), True)
 
@@ -45,8 +45,10 @@ def run_and_compare(shape, cfg, seed, *, page_tokens=32, max_prefill_rows=0, sig
     V = shape.vocab
     for turn in range(cfg.turns):
         live = rec["live_groups"][turn]
-        rows = [g * cfg.G + m for g in live for m in range(cfg.G)]
+        rows = rec["live_rows"][turn]
         assert list(ctx.sr_get_live_map()) == rows
+        if not rows:
+            continue
         obs = obs_fn(turn)[rows]
         ctx.sr_prefill_chunk(dev(obs), False)
         logits = torch.empty((len(rows), V), dtype=torch.float32, device="cuda")
@@ -71,7 +73,11 @@ def run_and_compare(shape, cfg, seed, *, page_tokens=32, max_prefill_rows=0, sig
         ctx.sr_get_actions(acts)
         torch.cuda.synchronize()
         assert np.array_equal(acts.cpu().numpy()[:, :K], rec["actions"][rows, :K])
-        if K in cfg.gate_turns:
+        if finish_fn is not None:
+            done = np.array([r in rec["finished"][turn] for r in rows], dtype=np.uint8)
+            assert ctx.sr_finish_sequences(done) == len(rows) - int(done.sum())
+            live = [g for g in live if any(r // cfg.G == g and not d for r, d in zip(rows, done))]
+        if K in cfg.gate_turns and live:
             sums = torch.empty(len(live), dtype=torch.int32, device="cuda")
             ret = torch.empty(len(live), dtype=torch.uint8, device="cuda")
             ctx.sr_gate(K, sums, ret)
@@ -378,8 +384,10 @@ def test_temperature_sampling_matches_checker():
     pos = cfg.prompt_len
     for turn in range(cfg.turns):
         live = rec["live_groups"][turn]
-        rows = [g * cfg.G + m for g in live for m in range(cfg.G)]
+        rows = rec["live_rows"][turn]
         assert list(ctx.sr_get_live_map()) == rows
+        if not rows:
+            continue
         ctx.sr_prefill_chunk(dev(obs_fn(turn)[rows]), False)
         pos += cfg.obs_len
         logits = torch.empty((len(rows), shape.vocab), dtype=torch.float32, device="cuda")
@@ -413,3 +421,23 @@ def test_temperature_sampling_matches_checker():
     print(f"sampling: worst |dlogit| = {worst:.3e}, draw mismatches on own logits = {own_mism}, "
           f"episode mismatches = {ep_mism}")
     assert worst <= LOGIT_TOL and own_mism == 0 and ep_mism == 0
+
+
+def test_members_finish_early_and_the_gate_compares_unequal_prefixes():
+    """Single members end at seeded steps; their groups go on without them (the prompt attention then walks
+    groups of unequal size), their saved prefixes stay in the gate, groups whose last member ends leave
+    un-retired, and the two-clause gate (tau_H = 0.5) retires mostly-finished groups."""
+    shape = synth.TINY
+    cfg = synth.EpisodeConfig("finishers", 6, 8, 64, 6, 16, 4, 16, (2, 4), 0.3, 0.34)
+    rng = np.random.default_rng(7)
+    ends = np.where(rng.random(cfg.n_groups * cfg.G) < 0.45, rng.integers(1, cfg.turns + 1, cfg.n_groups * cfg.G), 10 ** 6)
+    ends[2 * cfg.G:3 * cfg.G] = rng.integers(1, 4, cfg.G)            # a group whose members all end early
+    finish_fn = lambda K, r: ends[r] == K
+    for tau_H in (None, 0.5):
+        rec, stats, worst, mism, near = run_and_compare(shape, cfg, seed=2, finish_fn=finish_fn, tau_H=tau_H)
+        print(f"finishers tau_H={tau_H}: worst |dlogit| = {worst:.3e}, mismatches = {mism}, stats = {stats}")
+        assert worst <= LOGIT_TOL and mism == 0
+        assert stats["seqs_finished"] == sum(len(f) for f in rec["finished"]) > 0
+        assert stats["groups_retired"] == sum(sum(g["cut"].values()) for g in rec["gate"].values())
+        assert stats["pages_in_use"] == 0 or stats["n_live_seq"] > 0
+    assert any(any(n > 0 for n in g["n_done"].values()) for g in rec["gate"].values())

@@ -32,7 +32,7 @@ def run_gpu(acts, lens, d_L, tau_H, obs=None, end=None):
 def check(acts, lens, d_L=0.3, tau_H=0.5, obs=None, end=None):
     got = run_gpu(acts, lens, d_L, tau_H, obs, end)
     ref = oracle.signals_batch(acts, lens, d_L, tau_H, obs=obs, end_step=end)
-    for k in ("lev_scaled", "unique_prefix", "n_at_step", "unique_action", "unique_obs", "n_done", "cut_d", "cut_or"):
+    for k in ("lev_scaled", "lev_sum", "unique_prefix", "n_at_step", "unique_action", "unique_obs", "n_done", "cut_d", "cut_or"):
         assert np.array_equal(got[k], ref[k]), k
     assert np.array_equal(got["d_K"], ref["d_K"])
     assert np.array_equal(got["bigram_jaccard"], ref["bigram_jaccard"])

@@ -155,6 +155,34 @@ def test_episode_accounting_and_identical_groups():
     assert rec["final_live_groups"] == [g for g in range(cfg.n_groups) if not gate["cut"][g]]
 
 
+def test_episode_with_members_that_finish_early():
+    """A member that ends after step K generates K*A tokens and nothing more; the others are unaffected (their
+    tokens equal those of the run without finishers, since sequences do not interact); a group whose last
+    member ends leaves un-cut; the gate sees the ended members' shorter prefixes and their count."""
+    shape = synth.ModelShape(1, 32, 2, 1, 16, 48, 64)
+    w = synth.make_weights(shape, seed=3, sigma=0.3)
+    cfg = synth.EpisodeConfig("mini", 4, 3, 5, 4, 3, 2, 16, (3,), 0.3, 0.0)      # no converging groups
+    conv = synth.converging_groups(cfg, seed=1)
+    P = synth.prompts(cfg, shape.vocab, seed=1)
+    obs = lambda t: synth.observations(cfg, shape.vocab, 1, t, conv)
+    run = lambda **kw: oracle.run_episode(oracle.Model(w), P, obs, cfg.G, cfg.turns, cfg.act_len, cfg.action_mod,
+                                          cfg.gate_turns, 0.0, **kw)               # d_L = 0: the d clause never fires
+    base = run()
+    ends = {0: 1, 4: 2, 6: 1, 7: 2, 8: 3, 11: 4}                                   # group 2 (rows 6..8) ends entirely
+    rec = run(finish_fn=lambda K, r: ends.get(r) == K)
+    n_seq, A, T = cfg.n_groups * cfg.G, cfg.act_len, cfg.turns
+    assert rec["decoded_tokens"] == A * sum(min(ends.get(r, T), T) for r in range(n_seq))
+    assert rec["live_rows"][3] == [1, 2, 3, 5, 9, 10, 11] and rec["live_groups"][3] == [0, 1, 3]
+    for t in range(T):
+        rows = rec["live_rows"][t]
+        assert np.array_equal(rec["tokens"][t][:, rows], base["tokens"][t][:, rows])
+    assert rec["gate"][3]["n_done"] == {0: 1, 1: 1, 3: 0} and not any(rec["gate"][3]["cut"].values())
+    assert list(rec["end_step"][[0, 4, 8, 11]]) == [1, 2, 3, 4] and rec["end_step"][1] > T
+    # the two-clause gate retires the groups of which at least a third has ended
+    rec2 = run(finish_fn=lambda K, r: ends.get(r) == K, tau_H=1 / 3)
+    assert rec2["gate"][3]["cut"] == {0: True, 1: True, 3: False} and rec2["final_live_groups"] == [3]
+
+
 def test_bf16_contract_mode_is_off_by_default_and_small(small):
     """The contract mode only rounds activations to bf16: it must stay close to the exact evaluation
     (relative 2^-9 roundings) and must not leak into later exact evaluations."""

@@ -38,8 +38,10 @@ def brute(actions, obs, end, K):
     pairs = [(i, j) for i in range(G) for j in range(i + 1, G)]
     d = Fraction(0)
     jac = Fraction(0)
+    plain = 0
     for i, j in pairs:
         longer = max(len(pre[i]), len(pre[j]))
+        plain += lev_rec(pre[i], pre[j])
         if longer:
             d += Fraction(lev_rec(pre[i], pre[j]), longer)
         A = set(zip(pre[i][:-1], pre[i][1:]))
@@ -49,7 +51,8 @@ def brute(actions, obs, end, K):
     acts = [actions[i][K - 1] for i in at]
     counts = [acts.count(v) for v in sorted(set(acts))]
     return {
-        "d": d / len(pairs), "jac": jac / len(pairs), "unique_prefix": len(set(pre)), "n_at_step": len(at),
+        "d": d / len(pairs), "jac": jac / len(pairs), "lev_sum": plain, "unique_prefix": len(set(pre)),
+        "n_at_step": len(at),
         "unique_action": len(set(acts)), "unique_obs": len({obs[i][K - 1] for i in at}),
         "entropy": float(scipy_entropy(counts)) if counts else 0.0, "n_done": sum(e <= K for e in end),
     }
@@ -143,7 +146,7 @@ def test_equal_lengths_reduce_to_the_pinned_gate():
     sig = oracle.signals_batch(acts, lens, 0.3)
     for li, K in enumerate(lens):
         assert np.array_equal(sig["lev_scaled"][li], sums[li].astype(np.int64) * (oracle.lcm32() // K))
-        assert np.array_equal(sig["cut_d"][li], cut[li])
+        assert np.array_equal(sig["cut_d"][li], cut[li]) and np.array_equal(sig["lev_sum"][li], sums[li])
         assert np.allclose(sig["d_K"][li], sums[li] / (28 * K), rtol=0, atol=1e-15)
 
 
@@ -165,7 +168,7 @@ def test_against_the_definitions_worked_in_python(seed):
             assert Fraction(int(r["lev_scaled"]), oracle.lcm32() * P) == ref["d"]
             assert abs(r["d_K"] - float(ref["d"])) < 1e-14
             assert abs(r["bigram_jaccard"] - float(ref["jac"])) < 1e-14
-            for k in ("unique_prefix", "n_at_step", "unique_action", "unique_obs", "n_done"):
+            for k in ("unique_prefix", "n_at_step", "unique_action", "unique_obs", "n_done", "lev_sum"):
                 assert r[k] == ref[k], (k, K, g)
             assert abs(r["action_entropy"] - ref["entropy"]) < 1e-14
             assert r["cut_d"] == (ref["d"] < Fraction(3, 10))
