@@ -207,6 +207,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--workload", default="7b-g8-16groups", choices=["7b-g8-16groups", "tiny"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-score-pass", action="store_true", help="skip the teacher-forced scoring pass (extra object)")
     ap.add_argument("--layers", type=int, default=0,
                     help="counter collection only: truncate the model to this many layers (not a valid headline run)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -247,7 +248,8 @@ def main():
     if args.warmup > 0:
         run_episode(sr, torch, synth, shape, cfg, weights, min(args.warmup, cfg.turns), 0, None)
     res = run_episode(sr, torch, synth, shape, cfg, weights, turns, 0, profile_step=cfg.act_len // 2)
-    score = score_pass(sr, torch, synth, shape, cfg, weights, turns, 0) if args.layers == 0 else None
+    score = (score_pass(sr, torch, synth, shape, cfg, weights, turns, 0)
+             if args.layers == 0 and not args.no_score_pass else None)
     del weights
     torch.cuda.empty_cache()
 

@@ -176,23 +176,28 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_kernel(GemmArgs a) {
 // ---------------------------------------------------------------------------------------------
 // Prefill (M > 128) kernel: compute bound, so the tile is sized for the matrix cores.
 //
-// An 8-wavefront workgroup owns a 256 x 256 output tile; wavefront (wn, wm) of the 4 x 2 arrangement
-// computes 64 features x 128 rows with 32x32x16 MFMAs (128 accumulator registers).  Both operands go
-// through LDS in 64-wide k stages (two k-steps, 32 KiB of W + 32 KiB of X per stage, double buffered),
-// so every byte crosses the vector-memory path once per workgroup: 128 flop per byte fetched, against
-// 64 for a 128 x 128 tile with W read straight into registers, which ran out of L1 bandwidth.
-// Fragments are read from LDS one k-half ahead of their MFMAs.
+// A workgroup owns a 256 x 256 output tile.  Eight computing wavefronts in a 4 x 2 arrangement each take
+// 64 features x 128 rows with 32x32x16 MFMAs (128 accumulator registers); both operands reach them through
+// LDS, so every byte crosses the vector-memory path once per workgroup: 128 flop per byte fetched.
+// Two more wavefronts do nothing but fetch: one copies the W half, the other the X half of each k-step
+// (16 KiB each) from global memory straight into LDS with direct-to-LDS loads, up to three k-steps ahead
+// through four 32 KiB buffers, and join one workgroup barrier per k-step.  LDS itself is the landing zone
+// of the loads in flight, so the prefetch distance is no longer what a register staging set can hold, and
+// the computing wavefronts issue nothing but LDS reads and MFMAs (fragments of a k-half are read while the
+// MFMAs of the previous one run).  Ten wavefronts put three on two of the SIMDs: 168 registers each.
 // Workgroups are numbered so that the 32 that run together on one XCD form an 8 x 4 block of tiles
 // (2048 rows x 1024 features) whose operands they share through that XCD's L2.
 // ---------------------------------------------------------------------------------------------
-constexpr int kPfThreads = 512;
-constexpr int kPfStageVec = 4096;          // u32x4 per stage: [W: 2 k-steps x 16 tiles x 64][X: same]
-constexpr int kPfLdsBytes = 2 * kPfStageVec * 16;
+constexpr int kPfThreads = 640;            // 8 computing wavefronts + 2 loaders (W, X)
+constexpr int kPfKs = 1;                   // k-steps per stage
+constexpr int kPfStageVec = 2048 * kPfKs;  // u32x4 per stage: per k-step [W: 16 tiles x 64][X: 16 tiles x 64]
+constexpr int kPfBufs = 4;                 // stages in LDS: the loaders run up to three stages ahead
+constexpr int kPfLdsBytes = kPfBufs * kPfStageVec * 16;
 
 template <int EPI>
-__global__ __launch_bounds__(kPfThreads, 2) void gemm_prefill_kernel(GemmArgs a, int m_blocks, int n_blocks, int sm_count,
-                                                                     int st_count) {
-    extern __shared__ u32x4 pf_lds[];      // [2][kPfStageVec]
+__global__ __launch_bounds__(kPfThreads) void gemm_prefill_kernel(GemmArgs a, int m_blocks, int n_blocks, int sm_count,
+                                                                  int st_count) {
+    extern __shared__ u32x4 pf_lds[];      // [kPfBufs][kPfStageVec]
 
     // linear id -> XCD -> supertile -> tile
     const int L = blockIdx.x;
@@ -203,7 +208,47 @@ __global__ __launch_bounds__(kPfThreads, 2) void gemm_prefill_kernel(GemmArgs a,
     const int nb = (sg / sm_count) * 4 + (w >> 3);
     if (mb >= m_blocks || nb >= n_blocks) return;
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    const int n_stages = a.ks_total / kPfKs;
+    if (wave >= 8) {
+        // loaders (wavefront 8: W, wavefront 9: X): stage s lives in buffer s % kPfBufs; barrier s is passed by
+        // the computing wavefronts when they are done with stage s - 1 and by a loader when its half of stage s
+        // has landed; then buffer (s - 1) % kPfBufs is free and receives stage s + kPfBufs - 1
+        const bool is_x = wave == 9;
+        const u32x4 *src = is_x ? (const u32x4 *)a.X + (size_t)mb * 16 * 64 + lane
+                                : (const u32x4 *)a.W + ((size_t)(nb * 16) * a.ks_total) * 64 + lane;
+        const size_t ks_stride = is_x ? (size_t)a.mt_total * 64 : 64;
+        const size_t tile_stride = is_x ? 64 : (size_t)a.ks_total * 64;
+        const int dst0 = is_x ? 1024 : 0;
+        auto copy_stage = [&](int st, int buf) {
+            const int k0 = min(st, n_stages - 1) * kPfKs;
+#pragma unroll
+            for (int kk = 0; kk < kPfKs; ++kk)
+#pragma unroll
+                for (int t = 0; t < 16; ++t)
+                    __builtin_amdgcn_global_load_lds(
+                        (const __attribute__((address_space(1))) void *)(src + t * tile_stride + (size_t)(k0 + kk) * ks_stride),
+                        (__attribute__((address_space(3))) void *)&pf_lds[buf * kPfStageVec + kk * 2048 + dst0 + t * 64], 16, 0, 0);
+        };
+#pragma unroll
+        for (int i = 0; i < kPfBufs - 1; ++i) copy_stage(i, i);
+        int buf = kPfBufs - 1;
+        constexpr int kOut = 16 * kPfKs * (kPfBufs - 2);
+        constexpr int kWait = 0x0F70 | (kOut & 15) | ((kOut >> 4) << 14);     // all but the oldest stage may stay in flight
+        for (int s = 0; s < n_stages; ++s) {
+            __builtin_amdgcn_s_waitcnt(kWait);
+            asm volatile("" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            copy_stage(s + kPfBufs - 1, buf);
+            buf = buf == kPfBufs - 1 ? 0 : buf + 1;
+        }
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        return;
+    }
+
     const int wn = wave & 3, wm = wave >> 2;
     const int r32 = lane & 31, g2 = lane >> 5;
     const int sub = r32 >> 4, slot0 = (r32 & 15) + 16 * g2;
@@ -216,60 +261,26 @@ __global__ __launch_bounds__(kPfThreads, 2) void gemm_prefill_kernel(GemmArgs a,
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // staging: thread's r-th W vector is tile (tid + 512 r) / 128, k-step ((tid + 512 r) / 64) % 2
-    const u32x4 *wsrc[4];
-    int wdst[4];
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int v = tid + kPfThreads * r, nt = v >> 7, kk = (v >> 6) & 1;
-        wsrc[r] = (const u32x4 *)a.W + ((size_t)(nb * 16 + nt) * a.ks_total + kk) * 64 + lane;
-        wdst[r] = (kk * 16 + nt) * 64 + lane;
-    }
-    // X: vector (tid + 512 r): k-step (tid + 512 r) / 1024, position within the 16 row tiles % 1024
-    const size_t x_ks_stride = (size_t)a.mt_total * 64;
-    const u32x4 *xsrc = (const u32x4 *)a.X + (size_t)mb * 16 * 64;
-    u32x4 stw[4], stx[4];
-    const int n_stages = a.ks_total / 2;
+    // fragment offsets inside a k-step: W group i of this wavefront, X group j
+    const int woff = (wn * 4 + sub) * 64 + slot0;          // + i * 128 (two tiles) + h * 32
+    const int xoff = 1024 + (wm * 8 + sub) * 64 + slot0;   // + j * 128 + h * 32
 
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int v = tid + kPfThreads * r;
-        stw[r] = wsrc[r][0];
-        stx[r] = xsrc[(size_t)(v >> 10) * x_ks_stride + (v & 1023)];
-    }
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        pf_lds[wdst[r]] = stw[r];
-        pf_lds[2048 + tid + kPfThreads * r] = stx[r];
-    }
-    __syncthreads();
-
-    // fragment offsets inside a stage: W group i of this wavefront, X group j
-    const int woff = (wn * 4 + sub) * 64 + slot0;          // + i * 128 (two tiles) + kk * 1024 + h * 32
-    const int xoff = 2048 + (wm * 8 + sub) * 64 + slot0;   // + j * 128 + kk * 1024 + h * 32
-
-    for (int st = 0; st < n_stages; ++st) {
-        const int buf = st & 1;
-        const int nxt = min(st + 1, n_stages - 1);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int v = tid + kPfThreads * r;
-            stw[r] = wsrc[r][(size_t)nxt * 2 * 64];
-            stx[r] = xsrc[(size_t)(nxt * 2 + (v >> 10)) * x_ks_stride + (v & 1023)];
-        }
-        __builtin_amdgcn_sched_barrier(0);
+    int buf = 0;
+    for (int s = 0; s < n_stages; ++s) {
+        __syncthreads();                   // barrier s: stage s is in LDS
         const u32x4 *base = pf_lds + buf * kPfStageVec;
+        buf = buf == kPfBufs - 1 ? 0 : buf + 1;
         bf16x8 wf[2][2], xf[2][4];         // [parity][group]
 #pragma unroll
         for (int i = 0; i < 2; ++i) wf[0][i] = __builtin_bit_cast(bf16x8, base[woff + i * 128]);
 #pragma unroll
         for (int j = 0; j < 4; ++j) xf[0][j] = __builtin_bit_cast(bf16x8, base[xoff + j * 128]);
+        constexpr int Q = 2 * kPfKs;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {      // q = k-step * 2 + k-half
+        for (int q = 0; q < Q; ++q) {      // q = k-step * 2 + k-half
             __builtin_amdgcn_sched_barrier(0);
-            if (q + 1 < 4) {
-                const int o = ((q + 1) >> 1) * 1024 + ((q + 1) & 1) * 32;
+            if (q + 1 < Q) {
+                const int o = ((q + 1) >> 1) * 2048 + ((q + 1) & 1) * 32;
 #pragma unroll
                 for (int i = 0; i < 2; ++i) wf[(q + 1) & 1][i] = __builtin_bit_cast(bf16x8, base[woff + i * 128 + o]);
 #pragma unroll
@@ -280,7 +291,7 @@ __global__ __launch_bounds__(kPfThreads, 2) void gemm_prefill_kernel(GemmArgs a,
 #pragma unroll
                 for (int j = 0; j < 4; ++j)
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[q & 1][i], xf[q & 1][j], acc[i][j], 0, 0, 0);
-            if (q + 1 < 4) {
+            if (q + 1 < Q) {
 #pragma unroll
                 for (int f = 0; f < 6; ++f) {
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
@@ -290,12 +301,6 @@ __global__ __launch_bounds__(kPfThreads, 2) void gemm_prefill_kernel(GemmArgs a,
             }
         }
         __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            pf_lds[(buf ^ 1) * kPfStageVec + wdst[r]] = stw[r];
-            pf_lds[(buf ^ 1) * kPfStageVec + 2048 + tid + kPfThreads * r] = stx[r];
-        }
-        __syncthreads();
     }
 
     // accumulator (i, j): lane (r32 = row within the 32-row group, g2) holds, in register v,
@@ -380,10 +385,12 @@ int launch_gemm(const GemmArgs &a, GemmEpilogue epi, hipStream_t stream) {
     if (m_blocks * 8 > a.mt_total || a.splits < 1 || m_blocks > 65535 || a.splits > 65535 || a.ks_total % 16)
         return SR_E_ARG;
     if (m_blocks == 1 && a.wide) return launch_gemm_stream(a, epi, stream);
-    // wide outputs only: for N of a few thousand the 256 x 256 tiles leave too few workgroups per round
-    if (m_blocks > 1 && a.N >= 16384) {
-        const int mb256 = ceil_div(a.M, 256), nb256 = ceil_div(a.N, 256);
-        if (mb256 * 16 > a.mt_total || a.splits != 1) return SR_E_ARG;
+    // 256 x 256 tiles when they fill the 256 CUs well: always for wide outputs; for N of a few thousand only
+    // if the last round of workgroups is not mostly empty
+    const int mb256 = ceil_div(a.M, 256), nb256 = ceil_div(a.N, 256);
+    const int tiles256 = mb256 * nb256;
+    const bool fills = tiles256 * 8 >= ceil_div(tiles256, 256) * 256 * 7;      // >= 87.5 % of the slots used
+    if (m_blocks > 1 && a.splits == 1 && mb256 * 16 <= a.mt_total && (a.N >= 16384 || (a.N >= 2048 && fills))) {
         static bool attr_set = false;
         if (!attr_set) {
             SR_HIP(hipFuncSetAttribute((const void *)gemm_prefill_kernel<EPI_F32>,
