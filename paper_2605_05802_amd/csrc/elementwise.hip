@@ -29,6 +29,13 @@ __global__ __launch_bounds__(512) void resid_norm_kernel(NormArgs a) {
     const int nvec = a.H >> 3;                       // groups of 8 consecutive features
     float xv[2][8];
     float ss = 0.f;
+    // the gains do not depend on the reduction: fetch them first, so that the second pass starts from registers
+    uint4 graw[2];
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const int v = threadIdx.x + it * 512;
+        graw[it] = v < nvec ? *(const uint4 *)(a.gain + v * 8) : make_uint4(0, 0, 0, 0);
+    }
 
     const uint16_t *e = nullptr;
     if (a.embed) {
@@ -87,8 +94,7 @@ __global__ __launch_bounds__(512) void resid_norm_kernel(NormArgs a) {
         const int v = threadIdx.x + it * 512;
         if (v < nvec) {
             const float *f = xv[it];
-            const uint4 graw = *(const uint4 *)(a.gain + v * 8);
-            const uint32_t gw[4] = {graw.x, graw.y, graw.z, graw.w};
+            const uint32_t gw[4] = {graw[it].x, graw[it].y, graw[it].z, graw[it].w};
             float y[8];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -102,11 +108,12 @@ __global__ __launch_bounds__(512) void resid_norm_kernel(NormArgs a) {
     }
 }
 
-// One 64-thread block per (row, head).  Thread i owns the rotation pair (i, i + d/2).
+// One 64-thread block per (row, group of heads).  A thread owns four consecutive dims i .. i+3 of the low half of
+// a head and their rotation partners i + d/2 .. (16-byte loads of the fp32 partials); d/8 threads make a head.
 __global__ __launch_bounds__(64) void qkv_post_kernel(QkvPostArgs a) {
-    const int m = blockIdx.x, head = blockIdx.y, i = threadIdx.x;
-    const int half = a.d >> 1;
-    if (i >= half) return;
+    const int half = a.d >> 1, tph = half >> 2;               // threads per head
+    const int m = blockIdx.x, head = blockIdx.y * (64 / tph) + threadIdx.x / tph, i = (threadIdx.x % tph) * 4;
+    if (head >= a.n_q + 2 * a.n_kv) return;
     const int unit = m / a.chunk, ci = m - unit * a.chunk;
     const int pos = a.pos0 + ci;
     const int q_cols = a.n_q * a.d, kv_cols = a.n_kv * a.d;
@@ -117,52 +124,65 @@ __global__ __launch_bounds__(64) void qkv_post_kernel(QkvPostArgs a) {
     else if (head < a.n_q + a.n_kv) { kind = 1; h = head - a.n_q; col0 = q_cols + h * a.d; bias = a.bk ? a.bk + h * a.d : nullptr; }
     else { kind = 2; h = head - a.n_q - a.n_kv; col0 = q_cols + kv_cols + h * a.d; bias = a.bv ? a.bv + h * a.d : nullptr; }
 
-    float lo = 0.f, hi = 0.f;
+    f32x4 lo = {0.f, 0.f, 0.f, 0.f}, hi = {0.f, 0.f, 0.f, 0.f};
     {
-        const float *p0 = a.partials + (size_t)m * a.ld + col0;
+        const float *p0 = a.partials + (size_t)m * a.ld + col0 + i;
         int s = 0;
         for (; s + 4 <= a.n_partials; s += 4) {                  // independent loads, adds in split order
-            float pl[4], ph[4];
+            f32x4 pl[4], ph[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 const float *p = p0 + (size_t)(s + u) * a.partial_stride;
-                pl[u] = p[i];
-                ph[u] = p[i + half];
+                pl[u] = *(const f32x4 *)p;
+                ph[u] = *(const f32x4 *)(p + half);
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) { lo += pl[u]; hi += ph[u]; }
         }
         for (; s < a.n_partials; ++s) {
             const float *p = p0 + (size_t)s * a.partial_stride;
-            lo += p[i];
-            hi += p[i + half];
+            lo += *(const f32x4 *)p;
+            hi += *(const f32x4 *)(p + half);
         }
     }
-    if (bias) { lo += bf16_to_f32(bias[i]); hi += bf16_to_f32(bias[i + half]); }
-    if (kind != 2) {
-        const float c = a.rope_cos[(size_t)pos * half + i], s = a.rope_sin[(size_t)pos * half + i];
-        const float rlo = lo * c - hi * s, rhi = hi * c + lo * s;
-        lo = rlo; hi = rhi;
+    if (bias) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { lo[e] += bf16_to_f32(bias[i + e]); hi[e] += bf16_to_f32(bias[i + half + e]); }
     }
+    if (kind != 2) {
+        const f32x4 c = *(const f32x4 *)(a.rope_cos + (size_t)pos * half + i);
+        const f32x4 sn = *(const f32x4 *)(a.rope_sin + (size_t)pos * half + i);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const float rlo = lo[e] * c[e] - hi[e] * sn[e], rhi = hi[e] * c[e] + lo[e] * sn[e];
+            lo[e] = rlo; hi[e] = rhi;
+        }
+    }
+    const uint2 plo = make_uint2(pack_bf16x2(lo[0], lo[1]), pack_bf16x2(lo[2], lo[3]));
+    const uint2 phi = make_uint2(pack_bf16x2(hi[0], hi[1]), pack_bf16x2(hi[2], hi[3]));
     if (kind == 0) {
         uint16_t *q = a.q_out + ((size_t)m * a.n_q + h) * a.d;
-        q[i] = f32_to_bf16(lo);
-        q[i + half] = f32_to_bf16(hi);
+        *(uint2 *)(q + i) = plo;
+        *(uint2 *)(q + i + half) = phi;
         return;
     }
     const int page = a.page_table[(size_t)unit * a.pt_row_stride * a.pt_stride + pos / a.page_tokens];
     const int tok = pos % a.page_tokens, blk = tok >> 5, t = tok & 31;
     const size_t base = ((((size_t)page * a.n_kv + h) * (a.page_tokens >> 5)) + blk) * (size_t)(32 * a.d);
     if (kind == 1) {
+        // K block [d/32][32 tok][32]: four consecutive dims stay inside one 32-dim group
         uint16_t *k = a.kpool + base;
-        k[(((i >> 5) * 32 + t) << 5) + (i & 31)] = f32_to_bf16(lo);
+        *(uint2 *)(k + (((i >> 5) * 32 + t) << 5) + (i & 31)) = plo;
         const int i2 = i + half;
-        k[(((i2 >> 5) * 32 + t) << 5) + (i2 & 31)] = f32_to_bf16(hi);
+        *(uint2 *)(k + (((i2 >> 5) * 32 + t) << 5) + (i2 & 31)) = phi;
     } else {
         uint16_t *v = a.vpool + base;
         const int slot = 8 * ((t & 15) >> 2) + 4 * (t >> 4) + (t & 3);
-        v[i * 32 + slot] = f32_to_bf16(lo);
-        v[(i + half) * 32 + slot] = f32_to_bf16(hi);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            v[(i + e) * 32 + slot] = f32_to_bf16(lo[e]);
+            v[(i + half + e) * 32 + slot] = f32_to_bf16(hi[e]);
+        }
     }
 }
 
@@ -263,8 +283,9 @@ int launch_resid_norm(const NormArgs &a, hipStream_t stream) {
 
 int launch_qkv_post(const QkvPostArgs &a, hipStream_t stream) {
     if (a.rows <= 0) return SR_OK;
-    if (a.d > 128 || a.rows > 0x7FFFFFF) return SR_E_ARG;
-    qkv_post_kernel<<<dim3(a.rows, a.n_q + 2 * a.n_kv), dim3(64), 0, stream>>>(a);
+    if (a.d > 128 || a.d % 32 || a.rows > 0x7FFFFFF) return SR_E_ARG;
+    const int heads_per_block = 64 / (a.d / 8);                // d/8 threads per head
+    qkv_post_kernel<<<dim3(a.rows, ceil_div(a.n_q + 2 * a.n_kv, heads_per_block)), dim3(64), 0, stream>>>(a);
     SR_HIP(hipGetLastError());
     return SR_OK;
 }
