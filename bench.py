@@ -214,8 +214,9 @@ def main():
                     help="also run one plain 1 GiB device copy (reference for scaling HBM traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (groups are independent; see DESIGN.md for how the "
-              "path would shard). Run with --gpus 1.", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (groups are independent: the path would shard by "
+              "partitioning groups over GPUs with replicated weights and no collective). Run with --gpus 1.",
+              file=sys.stderr)
         sys.exit(2)
 
     import torch
