@@ -441,3 +441,81 @@ def test_members_finish_early_and_the_gate_compares_unequal_prefixes():
         assert stats["groups_retired"] == sum(sum(g["cut"].values()) for g in rec["gate"].values())
         assert stats["pages_in_use"] == 0 or stats["n_live_seq"] > 0
     assert any(any(n > 0 for n in g["n_done"].values()) for g in rec["gate"].values())
+
+
+def _episode_properties(cfg, turns, gate_turn):
+    """Runs `turns` turns of cfg at the 7B shape on the GPU alone and checks what must hold at any size:
+    converging groups (identical prompts and observations) stay bit-identical row by row, have pair-distance
+    sum 0 and are retired; token and page accounting follow the closed forms."""
+    shape = synth.QWEN7B
+    seed = 0
+    conv = synth.converging_groups(cfg, seed)
+    prompts = synth.prompts(cfg, shape.vocab, seed)
+    G, n_seq = cfg.G, cfg.n_groups * cfg.G
+    max_len = cfg.prompt_len + turns * (cfg.obs_len + cfg.act_len)
+    kv_tokens = cfg.n_groups * cfg.prompt_len + n_seq * (max_len - cfg.prompt_len + 64)
+    pool = int(kv_tokens * 57344 * 1.05) + (64 << 20)
+    ctx = sr.Context(shape, cfg.n_groups, G, cfg.threshold, page_tokens=64, max_seq_len=max_len, max_turns=turns,
+                     action_mod=cfg.action_mod, kv_pool_bytes=pool)
+    w = synth.make_weights_device(shape, seed=0)
+    ctx.sr_load_weights(*w)
+    del w
+    torch.cuda.empty_cache()
+    ctx.sr_prefill_chunk(dev(prompts), True)
+    rows = np.arange(n_seq)
+    n_cut = None
+    for turn in range(turns):
+        ctx.sr_prefill_chunk(dev(synth.observations(cfg, shape.vocab, seed, turn, conv)[rows]), False)
+        for _ in range(cfg.act_len):
+            ctx.sr_decode_step()
+        if turn + 1 == gate_turn:
+            logits = torch.empty((len(rows), shape.vocab), dtype=torch.float32, device="cuda")
+            ctx.sr_get_logits(logits)
+            acts = torch.empty((len(rows), turns), dtype=torch.int32, device="cuda")
+            ctx.sr_get_actions(acts)
+            sums = torch.empty(cfg.n_groups, dtype=torch.int32, device="cuda")
+            ret = torch.empty(cfg.n_groups, dtype=torch.uint8, device="cuda")
+            before = ctx.sr_stats()
+            ctx.sr_gate(gate_turn, sums, ret)
+            n_live = ctx.sr_retire_and_compact()
+            torch.cuda.synchronize()
+            lg, ac, s, r = logits.cpu().numpy(), acts.cpu().numpy(), sums.cpu().numpy(), ret.cpu().numpy()
+            assert np.all(np.isfinite(lg))
+            for g in range(cfg.n_groups):
+                if conv[g]:
+                    assert np.all(lg[g * G:(g + 1) * G] == lg[g * G])          # bit-identical rows
+                    assert np.all(ac[g * G:(g + 1) * G, :gate_turn] == ac[g * G, :gate_turn])
+                    assert s[g] == 0 and r[g] == 1
+            assert np.all((ac[:, :gate_turn] >= 0) & (ac[:, :gate_turn] < cfg.action_mod))
+            bound = oracle.gate_bound(cfg.threshold, G, gate_turn)
+            assert np.array_equal(r.astype(bool), s < bound)                    # Eq. 2 on the sums it reports
+            n_cut = int(r.sum())
+            assert n_live == cfg.n_groups - n_cut and n_cut >= conv.sum()
+            rows = ctx.sr_get_live_map()
+            assert list(rows) == [g * G + m for g in range(cfg.n_groups) if not r[g] for m in range(G)]
+            after = ctx.sr_stats()
+            ctx_len = cfg.prompt_len + gate_turn * (cfg.obs_len + cfg.act_len)
+            shared_pages = cfg.prompt_len // 64
+            priv_pages = -(-ctx_len // 64) - shared_pages
+            assert before["pages_in_use"] - after["pages_in_use"] == n_cut * (shared_pages + G * priv_pages)
+    stats = ctx.sr_stats()
+    f = (n_cut or 0) / cfg.n_groups
+    assert stats["decoded_tokens"] == round(n_seq * cfg.act_len * (turns - f * (turns - gate_turn)))
+    assert stats["seq_len"] == max_len
+    ctx.close()
+    return stats
+
+
+def test_full_size_benchmark_episode_properties():
+    """The benchmark's own episode (16 groups x G=8, prompt 1024, 20 turns of 64 + 32 tokens, gate after turn
+    10), far beyond what the CPU checker can follow: properties that hold at any size."""
+    stats = _episode_properties(synth.C3_EPISODE, synth.C3_EPISODE.turns, 10)
+    print(f"full-size episode: {stats}")
+    assert stats["groups_retired"] >= 6
+
+
+def test_512_sequence_batch_at_the_7b_shape():
+    """64 groups x G=8 = 512 rows (decode projections above one 128-row block at the full model width),
+    prompt 1024, three turns with the gate after the second."""
+    stats = _episode_properties(synth.C4_EPISODE, 3, 2)
+    print(f"512-row episode: {stats}")
