@@ -191,13 +191,19 @@ def cpu_baseline(synth, shape, acts, n_tokens=12):
     t0 = time.perf_counter()
     oracle.gate_batch(acts[:4096], [5, 10, 15], 0.3)
     gate_s = 4096 / (time.perf_counter() - t0)
+    rng = np.random.default_rng(1)
+    end = np.where(rng.random((4096, acts.shape[1])) < 0.35, rng.integers(1, acts.shape[2] + 1, size=(4096, acts.shape[1])),
+                   10 ** 6).astype(np.int32)
+    t0 = time.perf_counter()
+    oracle.signals_batch(acts[:4096], [5, 10, 15], 0.12, 0.9, obs=acts[:4096], end_step=end)
+    signals_s = 4096 / (time.perf_counter() - t0)
     cores = len(os.sched_getaffinity(0))
     threads = int(os.environ.get("OMP_NUM_THREADS", cores))
     return {"value": tok_s, "unit": "decoded tokens/s", "cores": min(threads, cores) if threads else cores,
             "kind": "oracle",
             "sample": f"{n_tokens - 1} single-sequence token forwards (fp64, context 1..{n_tokens - 1}) at the "
                       f"benchmark's model shape; gate: 4096 groups of the 65536-group workload",
-            "gate_groups_per_s": gate_s, "weight_generation_s": gen_s}
+            "gate_groups_per_s": gate_s, "signals_groups_per_s": signals_s, "weight_generation_s": gen_s}
 
 
 def main():

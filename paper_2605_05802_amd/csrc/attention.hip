@@ -173,49 +173,33 @@ __global__ __launch_bounds__(256, RT == 1 ? 3 : 2) void attn_kernel(AttnArgs a, 
             }
     };
 
-    if constexpr (RT == 1) {
-        // Software pipeline without spare registers: the K fragments of the next block are requested
-        // into the registers of the current ones as soon as the score MFMAs have consumed them, and
-        // the V fragments likewise after the P.V MFMAs, so 8 KiB per wavefront (d = 128) are in
-        // flight behind the softmax and behind the next block's scores.  The register budget stays
-        // low enough for three wavefronts per SIMD, so every item of a decode step is resident at once.
-        if (t_lo < t_hi) {
-            const size_t base = block_base(t_lo);
-            load_k(a.kpool + base);
-            load_v(a.vpool + base);
-        }
-        for (int t0 = t_lo; t0 < t_hi; t0 += 32) {          // t_lo is a multiple of 32
-            const int tn = t0 + 32 < t_hi ? t0 + 32 : t0;   // after the last block: harmless re-read
-            const size_t base_n = block_base(tn);
-            f32x4 s[RT][2];
-            scores(s);
-            // the scheduling fences keep each refill where it is written: right behind the last use
-            // of the registers it overwrites, a whole softmax (or score pass) ahead of its first use
-            __builtin_amdgcn_sched_barrier(0);
-            load_k(a.kpool + base_n);
-            __builtin_amdgcn_sched_barrier(0);
-            bf16x8 pf[RT];
-            float alpha[RT];
-            softmax(s, t0, pf, alpha);
-            accumulate(pf, alpha);
-            __builtin_amdgcn_sched_barrier(0);
-            load_v(a.vpool + base_n);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    } else {
-        // Two row tiles (prefill): the registers leave no room for a prefetch; K and V of a block are
-        // requested together at the top of its iteration.
-        for (int t0 = t_lo; t0 < t_hi; t0 += 32) {
-            const size_t base = block_base(t0);
-            load_k(a.kpool + base);
-            load_v(a.vpool + base);
-            f32x4 s[RT][2];
-            scores(s);
-            bf16x8 pf[RT];
-            float alpha[RT];
-            softmax(s, t0, pf, alpha);
-            accumulate(pf, alpha);
-        }
+    // Software pipeline without spare registers: the K fragments of the next block are requested
+    // into the registers of the current ones as soon as the score MFMAs have consumed them, and
+    // the V fragments likewise after the P.V MFMAs, so 8 KiB per wavefront (d = 128) are in
+    // flight behind the softmax and behind the next block's scores.  With one row tile (decode) the register
+    // budget stays low enough for three wavefronts per SIMD, so every item of a decode step is resident at once.
+    if (t_lo < t_hi) {
+        const size_t base = block_base(t_lo);
+        load_k(a.kpool + base);
+        load_v(a.vpool + base);
+    }
+    for (int t0 = t_lo; t0 < t_hi; t0 += 32) {          // t_lo is a multiple of 32
+        const int tn = t0 + 32 < t_hi ? t0 + 32 : t0;   // after the last block: harmless re-read
+        const size_t base_n = block_base(tn);
+        f32x4 s[RT][2];
+        scores(s);
+        // the scheduling fences keep each refill where it is written: right behind the last use
+        // of the registers it overwrites, a whole softmax (or score pass) ahead of its first use
+        __builtin_amdgcn_sched_barrier(0);
+        load_k(a.kpool + base_n);
+        __builtin_amdgcn_sched_barrier(0);
+        bf16x8 pf[RT];
+        float alpha[RT];
+        softmax(s, t0, pf, alpha);
+        accumulate(pf, alpha);
+        __builtin_amdgcn_sched_barrier(0);
+        load_v(a.vpool + base_n);
+        __builtin_amdgcn_sched_barrier(0);
     }
 
     // partial results: O^T tile lane (c, g) holds head dims dt*16 + 4g..4g+3 of row (rt, c)
