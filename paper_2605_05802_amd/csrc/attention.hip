@@ -202,12 +202,28 @@ __global__ __launch_bounds__(256, RT == 1 ? 3 : 2) void attn_kernel(AttnArgs a, 
         __builtin_amdgcn_sched_barrier(0);
     }
 
-    // partial results: O^T tile lane (c, g) holds head dims dt*16 + 4g..4g+3 of row (rt, c)
+    // results: O^T tile lane (c, g) holds head dims dt*16 + 4g..4g+3 of row (rt, c)
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
         float l = lrun[rt];
         l += __shfl_xor(l, 16, 64);
         l += __shfl_xor(l, 32, 64);
+        if (a.direct_out) {
+            // the only partial result of its rows: what the merge of one item computes, o / l (0 for an empty row)
+            if (limit[rt] < 0) continue;
+            const int row = rt * 16 + c;
+            const size_t qtok = (size_t)u_row0 + qtile * p.q_per_item + row / n_rep;
+            const int col = (kvh * n_rep + row % n_rep) * D + 4 * g;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                float r[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) r[e] = l > 0.f ? o[dt][rt][e] / l : 0.f;
+                *(uint2 *)(a.direct_out + frag_offset((int)qtok, col + dt * 16, a.out_mt_total)) =
+                    make_uint2(pack_bf16x2(r[0], r[1]), pack_bf16x2(r[2], r[3]));
+            }
+            continue;
+        }
         const size_t prow = (size_t)item * (16 * RT) + rt * 16 + c;
         float *po = p.part_o + prow * D;
         if (limit[rt] < 0) continue;        // padding row of the tile: the merge never reads it
@@ -296,6 +312,7 @@ int launch_attention(const AttnArgs &a, const AttnPhase *phases, int n_phases, h
             p.rt != phases[0].rt)
             return SR_E_ARG;
     }
+    if (a.direct_out && (n_phases != 1 || phases[0].n_splits != 1)) return SR_E_ARG;
     const long long n_items = n[0] + n[1];
     if (n_items <= 0) return SR_OK;
     if (n_items > 0x7FFFFFFF) return SR_E_ARG;

@@ -441,6 +441,9 @@ int forward(sr_ctx *c, const Pass &p, hipStream_t st) {
         add_phase(x);
     }
     if (part_rows > c->part_rows_cap) return SR_E_NOMEM;
+    // one partial result per query row: the attention kernel writes the merged output itself
+    aa.direct_out = n_ph == 1 && ph[0].n_splits == 1 ? (uint16_t *)c->attn_out : nullptr;
+    aa.out_mt_total = c->mt_total;
 
     for (int l = 0; l < s.n_layers; ++l) {
         const LayerW &w = c->L[l];
@@ -501,8 +504,10 @@ int forward(sr_ctx *c, const Pass &p, hipStream_t st) {
         aa.vpool = qa.vpool;
         SR_TRY(timed(c, p.decode ? SR_KC_ATTN_DECODE : SR_KC_ATTN_PREFILL, st,
                      [&] { return launch_attention(aa, ph, n_ph, st); }));
-        SR_TRY(timed(c, SR_KC_ATTN_MERGE, st,
-                     [&] { return launch_attn_merge(aa, ph, n_ph, M, c->attn_out, c->mt_total, st); }));
+        if (!aa.direct_out) {
+            SR_TRY(timed(c, SR_KC_ATTN_MERGE, st,
+                         [&] { return launch_attn_merge(aa, ph, n_ph, M, c->attn_out, c->mt_total, st); }));
+        }
 
         SR_TRY(timed(c, SR_KC_GEMM_O, st,
                      [&] { return gemm(c, c->attn_out, w.o, M, EPI_F32, c->partials, H, &sp, st); }));

@@ -210,6 +210,11 @@ struct AttnArgs {
     const int32_t *page_table;
     int pt_stride, page_tokens, n_q, n_kv, d;
     float scale;
+    // Non-null only when every query row gets exactly one partial result (one phase, one split): the attention
+    // kernel then normalises and writes the fragment-major bf16 output [query tokens][n_q*d] itself, with the
+    // arithmetic of the merge, and no merge is launched.
+    uint16_t *direct_out;
+    int out_mt_total;
 };
 // One launch over one or two phases (same rt); phases whose token range is empty contribute no work.
 int launch_attention(const AttnArgs &a, const AttnPhase *phases, int n_phases, hipStream_t stream);
