@@ -22,8 +22,10 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls are
  *     asynchronous on that stream unless stated otherwise.  One context must be driven
  *     from one stream at a time.
- *   - Batch rows are ordered group-major: live row r belongs to live group r / G, member
- *     r % G.  Retirement removes whole groups and keeps the order of the survivors.
+ *   - Batch rows are ordered group-major: while no sequence has finished early, live row r
+ *     belongs to live group r / G, member r % G.  Retirement removes whole groups,
+ *     sr_finish_sequences single members; both keep the order of the survivors
+ *     (sr_get_live_map names the original sequence of every row).
  *   - All live sequences have the same length at all times (lock-step turns).
  *   - bf16 tensors are raw 16-bit patterns; matrices are row-major [out_features][in_features].
  */
