@@ -55,12 +55,16 @@ def run_episode(sr, torch, synth, shape, cfg, weights, turns, seed, profile_step
 
     torch.cuda.synchronize()
     ev = lambda: torch.cuda.Event(enable_timing=True)
-    step_events, decode_meta = [], []
+    step_events, decode_meta, prefill_events = [], [], []
     t0 = time.perf_counter()
     ctx.sr_prefill_chunk(prompts, True)
     for turn in range(turns):
         obs = torch.from_numpy(obs_all[turn][live_rows]).cuda()
+        p0, p1 = ev(), ev()
+        p0.record()
         ctx.sr_prefill_chunk(obs, False)
+        p1.record()
+        prefill_events.append((p0, p1, len(live_rows) * cfg.obs_len))
         for a in range(cfg.act_len):
             prof = profile_step is not None and a == profile_step
             if prof:
@@ -84,7 +88,8 @@ def run_episode(sr, torch, synth, shape, cfg, weights, turns, seed, profile_step
     stats = ctx.sr_stats()
     step_ms = [a.elapsed_time(b) for a, b in step_events]
     ctx.close()
-    return {"wall_s": wall, "stats": stats, "step_ms": step_ms, "decode_meta": decode_meta,
+    prefill = [(a.elapsed_time(b), rows) for a, b, rows in prefill_events]
+    return {"wall_s": wall, "stats": stats, "step_ms": step_ms, "decode_meta": decode_meta, "prefill": prefill,
             "kernel_times": kernel_times, "shared_tokens": (cfg.prompt_len // 64) * 64}
 
 
@@ -290,6 +295,15 @@ def main():
         gbs.append(b / (ms * 1e-3) / 1e9)
     step_ms = [ms for (m, ms) in zip(res["decode_meta"], res["step_ms"]) if not m[2]]
 
+    # observation prefill against the matrix peak: projection flops only (attention not counted)
+    layer_params = shape.hidden * (shape.n_q_heads + 2 * shape.n_kv_heads) * shape.head_dim \
+        + shape.n_q_heads * shape.head_dim * shape.hidden + 3 * shape.hidden * shape.ffn
+    pf_rate = [2.0 * layer_params * shape.n_layers * rows / (ms * 1e-3) / 1e12 for ms, rows in res["prefill"]]
+    prefill_obj = {"ms_median": float(np.median([ms for ms, _ in res["prefill"]])),
+                   "projection_TFLOPs_median": float(np.median(pf_rate)),
+                   "frac_of_bf16_mfma_peak": float(np.median(pf_rate)) / 2500.0,
+                   "rows_first_turn": res["prefill"][0][1]} if res["prefill"] else None
+
     gate_gps, gate_ms, acts = gate_throughput(sr, torch, synth)
     sig_gps, sig_ms = signals_throughput(sr, torch, acts)
     out = {
@@ -309,6 +323,7 @@ def main():
                         "hbm_GBs_median": float(np.median(gbs)), "hbm_frac_median": float(np.median(gbs)) / HBM_PEAK_GBS,
                         "hbm_frac_best": float(np.max(gbs)) / HBM_PEAK_GBS,
                         "decode_only_tokens_per_s": decoded / (sum(res["step_ms"]) * 1e-3)},
+        "prefill_chunk": prefill_obj,
         "kernel_ms_per_profiled_step": {k: v[1] / max(len(rows), 1) for k, v in res["kernel_times"].items()},
         "gate": {"groups_per_s": gate_gps, "ms_per_launch": gate_ms, "workload": "65536 groups x G=8, prefixes 5/10/15"},
         "score_pass": score,
