@@ -136,6 +136,36 @@ def score_pass(sr, torch, synth, shape, cfg, weights, turns, seed):
                     "(transformer body + LM head on every action row + log-softmax gather)"}
 
 
+def sampling_steps(sr, torch, synth, shape, cfg, weights, seed, temperature=0.7, steps=8):
+    """Token selection at the paper's rollout temperature (Section 3.1): a few decode steps of the benchmark's batch
+    with Gumbel-max sampling, timed per kernel class, next to the same steps decoded greedily."""
+    G = cfg.G
+    max_len = cfg.prompt_len + cfg.obs_len + steps + 64
+    kv_tokens = cfg.n_groups * cfg.prompt_len + cfg.n_groups * G * (max_len - cfg.prompt_len + 64)
+    pool = int(kv_tokens * kv_bytes_per_token(shape) * 1.05) + (64 << 20)
+    out = {}
+    for name, temp in (("greedy", 0.0), ("sampled", temperature)):
+        ctx = sr.Context(shape, cfg.n_groups, G, cfg.threshold, page_tokens=64, max_seq_len=max_len, max_turns=4,
+                         action_mod=cfg.action_mod, kv_pool_bytes=pool, temperature=temp, sample_seed=seed)
+        embed, lm, fn, layers = weights
+        ctx.sr_load_weights(embed, lm, fn, layers)
+        conv = synth.converging_groups(cfg, seed)
+        ctx.sr_prefill_chunk(torch.from_numpy(synth.prompts(cfg, shape.vocab, seed)).cuda(), True)
+        ctx.sr_prefill_chunk(torch.from_numpy(synth.observations(cfg, shape.vocab, seed, 0, conv)).cuda(), False)
+        ctx.sr_decode_step()
+        ctx.sr_profile(True)
+        for _ in range(steps):
+            ctx.sr_decode_step()
+        ctx.sr_profile(False)
+        kt = ctx.sr_profile_read()
+        ctx.close()
+        out[name + "_select_ms_per_step"] = kt["argmax"][1] / steps
+        out[name + "_step_ms"] = sum(v[1] for v in kt.values()) / steps
+    out["temperature"] = temperature
+    out["note"] = "select = one kernel over [rows][vocab] fp32 logits: argmax, or argmax of logit/T + Gumbel noise"
+    return out
+
+
 def gate_throughput(sr, torch, synth, iters=20):
     acts, _ = synth.gate_actions(65536, 8, 30, 64, seed=0)
     a = torch.from_numpy(acts).cuda()
@@ -262,6 +292,7 @@ def main():
     res = run_episode(sr, torch, synth, shape, cfg, weights, turns, 0, profile_step=cfg.act_len // 2)
     score = (score_pass(sr, torch, synth, shape, cfg, weights, turns, 0)
              if args.layers == 0 and not args.no_score_pass else None)
+    sampling = sampling_steps(sr, torch, synth, shape, cfg, weights, 0) if args.layers == 0 else None
     del weights
     torch.cuda.empty_cache()
 
@@ -327,6 +358,7 @@ def main():
         "kernel_ms_per_profiled_step": {k: v[1] / max(len(rows), 1) for k, v in res["kernel_times"].items()},
         "gate": {"groups_per_s": gate_gps, "ms_per_launch": gate_ms, "workload": "65536 groups x G=8, prefixes 5/10/15"},
         "score_pass": score,
+        "sampling": sampling,
         "signals": {"groups_per_s": sig_gps, "ms_per_launch": sig_ms,
                     "workload": "same groups, 35 % of members finished early: Appendix-B signals + two-clause gate"},
         "episode": {k: res["stats"][k] for k in ("decoded_tokens", "prefill_tokens", "groups_retired", "pages_freed",
