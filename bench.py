@@ -246,7 +246,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="7b-g8-16groups", choices=["7b-g8-16groups", "tiny"])
+    ap.add_argument("--workload", default="7b-g8-16groups",
+                    choices=["7b-g8-16groups", "tiny", "7b-g8-64groups", "7b-g16-32groups"],
+                    help="default: the configuration the metric is quoted on; the two larger ones (512 sequences, "
+                         "90 and 120 GB of KV) are optional extra runs")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-score-pass", action="store_true", help="skip the teacher-forced scoring pass (extra object)")
     ap.add_argument("--layers", type=int, default=0,
@@ -270,6 +273,10 @@ def main():
 
     if args.workload == "tiny":
         shape, cfg = synth.TINY, synth.TINY_EPISODE
+    elif args.workload == "7b-g8-64groups":
+        shape, cfg = synth.QWEN7B, synth.C4_EPISODE
+    elif args.workload == "7b-g16-32groups":
+        shape, cfg = synth.QWEN7B, synth.C5_EPISODE
     else:
         shape, cfg = synth.QWEN7B, synth.C3_EPISODE
     turns = min(args.steps, cfg.turns)
@@ -291,8 +298,9 @@ def main():
         run_episode(sr, torch, synth, shape, cfg, weights, min(args.warmup, cfg.turns), 0, None)
     res = run_episode(sr, torch, synth, shape, cfg, weights, turns, 0, profile_step=cfg.act_len // 2)
     score = (score_pass(sr, torch, synth, shape, cfg, weights, turns, 0)
-             if args.layers == 0 and not args.no_score_pass else None)
-    sampling = sampling_steps(sr, torch, synth, shape, cfg, weights, 0) if args.layers == 0 else None
+             if args.layers == 0 and not args.no_score_pass and args.workload in ("7b-g8-16groups", "tiny") else None)
+    sampling = (sampling_steps(sr, torch, synth, shape, cfg, weights, 0)
+                if args.layers == 0 and args.workload in ("7b-g8-16groups", "tiny") else None)
     del weights
     torch.cuda.empty_cache()
 
@@ -305,6 +313,13 @@ def main():
     mean_rows = float(np.mean([m[0] for m in rows])) if rows else 0.0
     gu_bytes = 2 * (2 * shape.ffn * shape.hidden) + mean_rows * shape.hidden * 2 + mean_rows * shape.ffn * 2
     achieved = gu_bytes / (avg_ms * 1e-3) / 1e9 if avg_ms > 0 else 0.0
+    roofline = {"bound": "hbm", "kernel": "gemm_stream_kernel<EPI_SWIGLU, 5, MT32, 8> (decode gate|up projection)",
+                "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS}
+    if mean_rows > 128:
+        # more than 128 rows per step: the projection runs on a tiled prefill kernel and is bound by the matrix cores
+        tf = 2.0 * mean_rows * 2 * shape.ffn * shape.hidden / (avg_ms * 1e-3) / 1e12 if avg_ms > 0 else 0.0
+        roofline = {"bound": "mfma", "kernel": "decode gate|up projection at more than 128 rows (128 x 128- or 256 x 256-tile kernel)",
+                    "achieved": tf, "peak": 2500.0, "unit": "TFLOP/s", "frac": tf / 2500.0}
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
@@ -338,7 +353,7 @@ def main():
     gate_gps, gate_ms, acts = gate_throughput(sr, torch, synth)
     sig_gps, sig_ms = signals_throughput(sr, torch, acts)
     out = {
-        "metric": "decoded tokens/s at Qwen2.5-7B shape, G=8 (whole gated episode: prompt prefill, per-turn "
+        "metric": f"decoded tokens/s at Qwen2.5-7B shape, G={cfg.G} (whole gated episode: prompt prefill, per-turn "
                   "observation prefill, greedy decode, gate, compaction)",
         "value": decoded / wall, "unit": "tokens/s", "n_gpus": 1, "steps": turns, "warmup": args.warmup,
         "ms_per_step": 1e3 * wall / turns, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -346,10 +361,8 @@ def main():
         "config": {"workload": cfg.name, "layers": shape.n_layers, "hidden": shape.hidden, "groups": cfg.n_groups,
                    "G": cfg.G, "prompt": cfg.prompt_len, "turns": turns, "obs": cfg.obs_len, "act": cfg.act_len,
                    "gate_turns": list(cfg.gate_turns), "threshold": cfg.threshold},
-        "roofline": {"bound": "hbm", "kernel": "gemm_stream_kernel<EPI_SWIGLU, 5, MT32, 8> (decode gate|up projection)",
-                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": traffic, "avg_launch_ms": avg_ms, "launches_timed": launches,
-                     "algorithmic_bytes_per_launch": gu_bytes},
+        "roofline": dict(roofline, traffic=traffic if mean_rows <= 128 else None, avg_launch_ms=avg_ms,
+                         launches_timed=launches, algorithmic_bytes_per_launch=gu_bytes),
         "decode_step": {"ms_median": float(np.median(step_ms)), "ms_min": float(np.min(step_ms)),
                         "hbm_GBs_median": float(np.median(gbs)), "hbm_frac_median": float(np.median(gbs)) / HBM_PEAK_GBS,
                         "hbm_frac_best": float(np.max(gbs)) / HBM_PEAK_GBS,

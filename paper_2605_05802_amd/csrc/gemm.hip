@@ -385,12 +385,15 @@ int launch_gemm(const GemmArgs &a, GemmEpilogue epi, hipStream_t stream) {
     if (m_blocks * 8 > a.mt_total || a.splits < 1 || m_blocks > 65535 || a.splits > 65535 || a.ks_total % 16)
         return SR_E_ARG;
     if (m_blocks == 1 && a.wide) return launch_gemm_stream(a, epi, stream);
-    // 256 x 256 tiles when they fill the 256 CUs well: always for wide outputs; for N of a few thousand only
-    // if the last round of workgroups is not mostly empty
+    // 256 x 256 tiles (one workgroup per CU, whole rounds of 256) or 128 x 128 tiles (two workgroups per CU, which
+    // drain almost continuously): a round of the large tiles costs about as much as 720 of the small ones
+    // (measured at K = 3584: 112 us a round against 0.166 us a tile, both proportional to K), so the large tiles win
+    // where their last round is well filled -- every prefill projection but the thinnest -- and lose for a few
+    // hundred rows, where the second row block or the second round is mostly empty.
     const int mb256 = ceil_div(a.M, 256), nb256 = ceil_div(a.N, 256);
-    const int tiles256 = mb256 * nb256;
-    const bool fills = tiles256 * 8 >= ceil_div(tiles256, 256) * 256 * 7;      // >= 87.5 % of the slots used
-    if (m_blocks > 1 && a.splits == 1 && mb256 * 16 <= a.mt_total && (a.N >= 16384 || (a.N >= 2048 && fills))) {
+    const long long rounds256 = ceil_div(mb256 * nb256, 256);
+    const long long tiles128 = (long long)m_blocks * ceil_div(a.N, 128);
+    if (m_blocks > 1 && a.splits == 1 && mb256 * 16 <= a.mt_total && rounds256 * 720 <= tiles128) {
         static bool attr_set = false;
         if (!attr_set) {
             SR_HIP(hipFuncSetAttribute((const void *)gemm_prefill_kernel<EPI_F32>,
