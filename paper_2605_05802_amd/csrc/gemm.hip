@@ -379,40 +379,33 @@ int launch_pack_rows(const uint16_t *src, int n_rows, int K, uint16_t *dst, int 
     return SR_OK;
 }
 
-int launch_gemm(const GemmArgs &a, GemmEpilogue epi, hipStream_t stream) {
-    if (a.M <= 0) return SR_OK;
-    const int m_blocks = ceil_div(a.M, 128);
-    if (m_blocks * 8 > a.mt_total || a.splits < 1 || m_blocks > 65535 || a.splits > 65535 || a.ks_total % 16)
-        return SR_E_ARG;
-    if (m_blocks == 1 && a.wide) return launch_gemm_stream(a, epi, stream);
-    // 256 x 256 tiles (one workgroup per CU, whole rounds of 256) or 128 x 128 tiles (two workgroups per CU, which
-    // drain almost continuously): a round of the large tiles costs about as much as 720 of the small ones
-    // (measured at K = 3584: 112 us a round against 0.166 us a tile, both proportional to K), so the large tiles win
-    // where their last round is well filled -- every prefill projection but the thinnest -- and lose for a few
-    // hundred rows, where the second row block or the second round is mostly empty.
-    const int mb256 = ceil_div(a.M, 256), nb256 = ceil_div(a.N, 256);
-    const long long rounds256 = ceil_div(mb256 * nb256, 256);
-    const long long tiles128 = (long long)m_blocks * ceil_div(a.N, 128);
-    if (m_blocks > 1 && a.splits == 1 && mb256 * 16 <= a.mt_total && rounds256 * 720 <= tiles128) {
-        static bool attr_set = false;
-        if (!attr_set) {
-            SR_HIP(hipFuncSetAttribute((const void *)gemm_prefill_kernel<EPI_F32>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kPfLdsBytes));
-            SR_HIP(hipFuncSetAttribute((const void *)gemm_prefill_kernel<EPI_SWIGLU>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kPfLdsBytes));
-            attr_set = true;
-        }
-        const int sm_count = ceil_div(mb256, 8), sn_count = ceil_div(nb256, 4);
-        const int st_count = sm_count * sn_count;
-        dim3 pgrid((unsigned)(ceil_div(st_count, 8) * 8 * 32)), pblock(kPfThreads);
-        if (epi == EPI_F32)
-            gemm_prefill_kernel<EPI_F32><<<pgrid, pblock, kPfLdsBytes, stream>>>(a, mb256, nb256, sm_count, st_count);
-        else
-            gemm_prefill_kernel<EPI_SWIGLU><<<pgrid, pblock, kPfLdsBytes, stream>>>(a, mb256, nb256, sm_count, st_count);
-        SR_HIP(hipGetLastError());
-        return SR_OK;
+namespace {
+
+// 256 x 256 tiles over all of `a`
+int launch_tiles256(const GemmArgs &a, GemmEpilogue epi, hipStream_t stream) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        SR_HIP(hipFuncSetAttribute((const void *)gemm_prefill_kernel<EPI_F32>,
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, kPfLdsBytes));
+        SR_HIP(hipFuncSetAttribute((const void *)gemm_prefill_kernel<EPI_SWIGLU>,
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, kPfLdsBytes));
+        attr_set = true;
     }
-    const int n_blocks = ceil_div(a.N, 128);
+    const int mb256 = ceil_div(a.M, 256), nb256 = ceil_div(a.N, 256);
+    const int sm_count = ceil_div(mb256, 8), sn_count = ceil_div(nb256, 4);
+    const int st_count = sm_count * sn_count;
+    dim3 pgrid((unsigned)(ceil_div(st_count, 8) * 8 * 32)), pblock(kPfThreads);
+    if (epi == EPI_F32)
+        gemm_prefill_kernel<EPI_F32><<<pgrid, pblock, kPfLdsBytes, stream>>>(a, mb256, nb256, sm_count, st_count);
+    else
+        gemm_prefill_kernel<EPI_SWIGLU><<<pgrid, pblock, kPfLdsBytes, stream>>>(a, mb256, nb256, sm_count, st_count);
+    SR_HIP(hipGetLastError());
+    return SR_OK;
+}
+
+// 128 x 128 tiles over all of `a` (also the 4-wavefront decode kernel when the batch is one row block)
+int launch_tiles128(const GemmArgs &a, GemmEpilogue epi, hipStream_t stream) {
+    const int m_blocks = ceil_div(a.M, 128), n_blocks = ceil_div(a.N, 128);
     dim3 grid(n_blocks, m_blocks, epi == EPI_F32 ? a.splits : 1), block(kThreads);
     if (m_blocks == 1) {
         if (epi == EPI_F32) gemm_kernel<EPI_F32, true><<<grid, block, 0, stream>>>(a);
@@ -423,6 +416,65 @@ int launch_gemm(const GemmArgs &a, GemmEpilogue epi, hipStream_t stream) {
     }
     SR_HIP(hipGetLastError());
     return SR_OK;
+}
+
+// `a` restricted to the packed columns from c0 (a multiple of 256) on
+GemmArgs columns_from(const GemmArgs &a, GemmEpilogue epi, int c0) {
+    GemmArgs b = a;
+    b.N = a.N - c0;
+    b.W = a.W + (size_t)(c0 / 16) * a.ks_total * 64;
+    if (epi == EPI_F32) {
+        b.out = (float *)a.out + c0;
+    } else {                                   // output feature c0 / 2 of the fragment-major matrix
+        b.out = (uint16_t *)a.out + frag_offset(0, c0 / 2, a.mt_total);
+        b.ld_out = a.ld_out - c0 / 2;
+    }
+    return b;
+}
+
+}  // namespace
+
+int launch_gemm(const GemmArgs &a, GemmEpilogue epi, hipStream_t stream) {
+    if (a.M <= 0) return SR_OK;
+    const int m_blocks = ceil_div(a.M, 128);
+    if (m_blocks * 8 > a.mt_total || a.splits < 1 || m_blocks > 65535 || a.splits > 65535 || a.ks_total % 16)
+        return SR_E_ARG;
+    if (m_blocks == 1 && a.wide) return launch_gemm_stream(a, epi, stream);
+    const int mb256 = ceil_div(a.M, 256), nb256 = ceil_div(a.N, 256);
+    if (m_blocks > 1 && a.splits == 1 && mb256 * 16 <= a.mt_total) {
+        const int tiles256 = mb256 * nb256;
+        if (a.M > 1024) {
+            // Prefill-sized batches: 256 x 256 tiles when they fill the 256 CUs well -- always for wide outputs; for
+            // N of a few thousand only if the last round of workgroups is not mostly empty.
+            const bool fills = tiles256 * 8 >= ceil_div(tiles256, 256) * 256 * 7;      // >= 87.5 % of the slots used
+            if (a.N >= 16384 || (a.N >= 2048 && fills)) return launch_tiles256(a, epi, stream);
+            return launch_tiles128(a, epi, stream);
+        }
+        // A few hundred rows (decode steps of a large batch).  256 x 256 tiles run one workgroup per CU in whole
+        // rounds of 256; 128 x 128 tiles run two per CU and drain almost continuously.  Measured at 304 and 512
+        // rows, K = 3584: 112 us a round against 0.166 us a small tile (both proportional to K), i.e. a round costs
+        // what 720 small tiles do, and a launch of small tiles at least what 200 of them do.  Third choice: whole
+        // rounds of large tiles over the first columns and small tiles over the rest, in two launches.
+        const long long cost256 = (long long)ceil_div(tiles256, 256) * 720;
+        long long cost128 = (long long)m_blocks * ceil_div(a.N, 128);
+        if (cost128 < 200) cost128 = 200;
+        const int cols_per_round = 256 / mb256;                   // column blocks of 256 in one round of large tiles
+        const int rounds_a = nb256 / cols_per_round;
+        const int c0 = rounds_a * cols_per_round * 256;           // first column of the small-tile part
+        long long cost_mix = -1;
+        if (rounds_a > 0 && c0 < a.N) {
+            const long long rest = (long long)m_blocks * ceil_div(a.N - c0, 128);
+            cost_mix = (long long)rounds_a * 720 + (rest > 200 ? rest : 200) + 20;
+        }
+        if (cost_mix >= 0 && cost_mix < cost256 && cost_mix < cost128) {
+            GemmArgs first = a;
+            first.N = c0;
+            SR_TRY(launch_tiles256(first, epi, stream));
+            return launch_tiles128(columns_from(a, epi, c0), epi, stream);
+        }
+        if (cost256 <= cost128) return launch_tiles256(a, epi, stream);
+    }
+    return launch_tiles128(a, epi, stream);
 }
 
 }  // namespace sr

@@ -240,6 +240,20 @@ def test_wide_shapes_exercise_every_gemm_variant():
     assert worst <= LOGIT_TOL and mism == 0
 
 
+def test_mid_size_batch_takes_mixed_tiles_and_split_k():
+    """512 rows per decode step, 304 after the gate (the shape of the 64-group configuration): between 129 and
+    1024 rows the wide gate|up projection (here 33 792 packed columns) runs whole rounds of 256 x 256 tiles over
+    its first columns and 128 x 128 tiles over the rest, and the thin projections are split along K; every logit
+    of every row is compared with the checker."""
+    shape = synth.ModelShape(1, 256, 4, 2, 64, 16896, 1024)
+    cfg = synth.EpisodeConfig("mid", 64, 8, 16, 2, 2, 2, 64, (1,), 0.3, 0.4)
+    rec, stats, worst, mism, near = run_and_compare(shape, cfg, seed=4, page_tokens=32, kv_pool_bytes=1 << 28)
+    print(f"mid: worst |dlogit| = {worst:.3e}, mismatches = {mism}, near ties = {near}, "
+          f"rows after the gate = {stats['n_live_seq']}")
+    assert 128 < stats["n_live_seq"] < 512
+    assert worst <= LOGIT_TOL and mism == 0
+
+
 def test_7b_shape_sampled_sequences():
     """Full Qwen2.5-7B shape (28 layers, hidden 3584, 28q/4kv x 128, FFN 18944, vocab 152064) in the
     benchmark's launch configuration (16 groups x G=8 = 128 rows, 64-token pages).  The CPU checker
