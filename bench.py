@@ -206,23 +206,38 @@ def signals_throughput(sr, torch, acts, iters=20):
     return n_groups / (ms * 1e-3), ms
 
 
-def cpu_baseline(synth, shape, acts, n_tokens=12):
-    """The CPU checker, as it stands, on a bounded sample: n_tokens single-sequence token forwards at
-    the benchmark's model shape (weights generated on the host by the same seeded generator), plus the
-    gate on 4096 groups of the gate workload."""
+def cpu_baseline(synth, shape, cfg, acts, turns=2):
+    """The CPU checker, as it stands, on a bounded sample of the same workload: one sequence of the benchmark's
+    model shape (weights generated on the host by the same seeded generator) through `turns` turns -- its share of
+    the group's prompt, then per turn the observation chunk and the action tokens one by one -- plus the gate and
+    the signals on 4096 groups of the gate workload."""
     import oracle
     t0 = time.perf_counter()
     w = synth.make_weights(shape, seed=0)
     gen_s = time.perf_counter() - t0
     model = oracle.Model(w)
-    seq = model.new_seq(n_tokens + 1)
-    toks = synth.uniform_ids(n_tokens, 0, 777, shape.vocab)
+    # a member's share of the shared prompt, per turn of the whole episode
+    prompt_share = max(1, round(cfg.prompt_len * turns / (cfg.G * cfg.turns)))
+    n_fwd = prompt_share + turns * (cfg.obs_len + cfg.act_len)
+    seq = model.new_seq(n_fwd + 2)
+    toks = synth.uniform_ids(n_fwd + 1, 0, 777, shape.vocab)
     seq.forward(toks[:1])                                   # page the weights in
+    pos = 1
     t0 = time.perf_counter()
-    for t in toks[1:]:
-        seq.forward([t])
+    seq.forward(toks[pos:pos + prompt_share])
+    pos += prompt_share
+    dec_s = 0.0
+    for _ in range(turns):
+        seq.forward(toks[pos:pos + cfg.obs_len])
+        pos += cfg.obs_len
+        t1 = time.perf_counter()
+        for t in toks[pos:pos + cfg.act_len]:
+            seq.forward([t])
+        dec_s += time.perf_counter() - t1
+        pos += cfg.act_len
     dt = time.perf_counter() - t0
-    tok_s = (n_tokens - 1) / dt
+    decoded = turns * cfg.act_len
+    tok_s = decoded / dt
     t0 = time.perf_counter()
     oracle.gate_batch(acts[:4096], [5, 10, 15], 0.3)
     gate_s = 4096 / (time.perf_counter() - t0)
@@ -236,8 +251,11 @@ def cpu_baseline(synth, shape, acts, n_tokens=12):
     threads = int(os.environ.get("OMP_NUM_THREADS", cores))
     return {"value": tok_s, "unit": "decoded tokens/s", "cores": min(threads, cores) if threads else cores,
             "kind": "oracle",
-            "sample": f"{n_tokens - 1} single-sequence token forwards (fp64, context 1..{n_tokens - 1}) at the "
-                      f"benchmark's model shape; gate: 4096 groups of the 65536-group workload",
+            "sample": f"one sequence of the benchmark's model shape in fp64: {prompt_share} prompt tokens (a member's "
+                      f"share of the group prompt for {turns} of {cfg.turns} turns), then {turns} turns of {cfg.obs_len} "
+                      f"observation + {cfg.act_len} decoded tokens; value = decoded tokens / whole-sample time "
+                      f"({dt:.1f} s); gate and signals: 4096 groups of the 65536-group workload",
+            "decode_only_tokens_per_s": decoded / dec_s,
             "gate_groups_per_s": gate_s, "signals_groups_per_s": signals_s, "weight_generation_s": gen_s}
 
 
@@ -381,7 +399,7 @@ def main():
     }
     if not args.no_cpu_baseline:
         cshape = shape
-        out["cpu_baseline"] = cpu_baseline(synth, cshape, acts)
+        out["cpu_baseline"] = cpu_baseline(synth, cshape, cfg, acts)
     print(json.dumps(out))
 
 
