@@ -240,6 +240,22 @@ def test_wide_shapes_exercise_every_gemm_variant():
     assert worst <= LOGIT_TOL and mism == 0
 
 
+@pytest.mark.parametrize("n_q,n_kv,d,hidden,ffn,vocab,G,page", [
+    (4, 4, 64, 256, 176, 272, 5, 32),      # one query head per kv head, FFN and vocabulary not multiples of 128
+    (4, 1, 64, 160, 304, 1008, 3, 64),     # query width (256) different from the hidden size, 4 query heads per kv head
+    (16, 1, 64, 512, 528, 512, 16, 128),   # 16 query heads per kv head and 16 members per group: the limits
+    (12, 4, 128, 384, 1040, 2064, 7, 128), # head size 128, 3 query heads per kv head, 128-token pages
+])
+def test_shapes_at_the_edges_of_what_is_supported(n_q, n_kv, d, hidden, ffn, vocab, G, page):
+    """Index arithmetic off the beaten path: grouped-query ratios 1 .. 16, group sizes that are not powers of two,
+    widths that do not fill the last tile, a prompt that ends inside a page."""
+    shape = synth.ModelShape(2, hidden, n_q, n_kv, d, ffn, vocab)
+    cfg = synth.EpisodeConfig("edge", 3, G, 37, 2, 5, 3, 16, (1,), 0.3, 0.4)
+    rec, stats, worst, mism, near = run_and_compare(shape, cfg, seed=11, page_tokens=page, kv_pool_bytes=1 << 27)
+    print(f"edge {n_q}/{n_kv}x{d} G={G}: worst |dlogit| = {worst:.3e}, mismatches = {mism}, near ties = {near}")
+    assert worst <= LOGIT_TOL and mism == 0
+
+
 def test_mid_size_batch_takes_mixed_tiles_and_split_k():
     """512 rows per decode step, 304 after the gate (the shape of the 64-group configuration): between 129 and
     1024 rows the wide gate|up projection (here 33 792 packed columns) runs whole rounds of 256 x 256 tiles over
