@@ -256,6 +256,18 @@ def test_shapes_at_the_edges_of_what_is_supported(n_q, n_kv, d, hidden, ffn, voc
     assert worst <= LOGIT_TOL and mism == 0
 
 
+def test_long_shared_prompt_in_several_passes():
+    """A 9001-token prompt: prefilled in two passes (more rows than one pass takes), 282 pages of 32 tokens per
+    sequence ending inside a page, RoPE positions past 9000, and more shared-prompt splits in decode than the
+    attention kernel's cap."""
+    shape = synth.TINY
+    cfg = synth.EpisodeConfig("long", 1, 2, 9001, 1, 40, 3, 16, (), 0.3, 0.0)
+    rec, stats, worst, mism, near = run_and_compare(shape, cfg, seed=5, page_tokens=32, kv_pool_bytes=1 << 28)
+    print(f"long: worst |dlogit| = {worst:.3e}, mismatches = {mism}, near ties = {near}")
+    assert stats["seq_len"] == 9001 + 40 + 3
+    assert worst <= LOGIT_TOL and mism == 0
+
+
 def test_mid_size_batch_takes_mixed_tiles_and_split_k():
     """512 rows per decode step, 304 after the gate (the shape of the 64-group configuration): between 129 and
     1024 rows the wide gate|up projection (here 33 792 packed columns) runs whole rounds of 256 x 256 tiles over
