@@ -70,3 +70,20 @@ def test_product_never_touches_the_checker():
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text.lower(), f
                 assert "sro_" not in text, f
+
+
+def test_bench_refuses_more_than_one_gpu_and_fails_loudly_without_one():
+    """`bench.py --gpus 2` exits with a message before touching any device (this build runs on one GPU);
+    without a GPU the default run exits non-zero instead of falling back to the CPU."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0 and "one GPU" in (r.stderr + r.stdout)
+    assert not r.stdout.strip().startswith("{")
+    import torch
+    if not torch.cuda.is_available():
+        r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--steps", "1"], capture_output=True,
+                           text=True, timeout=300)
+        assert r.returncode != 0 and "no GPU" in r.stderr and not r.stdout.strip().startswith("{")
