@@ -452,10 +452,11 @@ int launch_gemm(const GemmArgs &a, GemmEpilogue epi, hipStream_t stream) {
         }
         // A few hundred rows (decode steps of a large batch).  256 x 256 tiles run one workgroup per CU in whole
         // rounds of 256; 128 x 128 tiles run two per CU and drain almost continuously.  Measured at 304 and 512
-        // rows, K = 3584: 112 us a round against 0.166 us a small tile (both proportional to K), i.e. a round costs
-        // what 720 small tiles do, and a launch of small tiles at least what 200 of them do.  Third choice: whole
-        // rounds of large tiles over the first columns and small tiles over the rest, in two launches.
-        const long long cost256 = (long long)ceil_div(tiles256, 256) * 720;
+        // rows, K = 3584: 150 us a round (the weights come from HBM: only two row blocks share them) against 0.166 us
+        // a small tile, both proportional to K, i.e. a round costs what 900 small tiles do, and a launch of small
+        // tiles at least what 200 of them do.  Third choice: whole rounds of large tiles over the first columns and
+        // small tiles over the rest, in two launches.
+        const long long cost256 = (long long)ceil_div(tiles256, 256) * 900;
         long long cost128 = (long long)m_blocks * ceil_div(a.N, 128);
         if (cost128 < 200) cost128 = 200;
         const int cols_per_round = 256 / mb256;                   // column blocks of 256 in one round of large tiles
@@ -464,7 +465,7 @@ int launch_gemm(const GemmArgs &a, GemmEpilogue epi, hipStream_t stream) {
         long long cost_mix = -1;
         if (rounds_a > 0 && c0 < a.N) {
             const long long rest = (long long)m_blocks * ceil_div(a.N - c0, 128);
-            cost_mix = (long long)rounds_a * 720 + (rest > 200 ? rest : 200) + 20;
+            cost_mix = (long long)rounds_a * 900 + (rest > 200 ? rest : 200) + 20;
         }
         if (cost_mix >= 0 && cost_mix < cost256 && cost_mix < cost128) {
             GemmArgs first = a;
