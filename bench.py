@@ -276,7 +276,7 @@ def main():
                     help="also run one plain 1 GiB device copy (reference for scaling HBM traffic counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (groups are independent: the path would shard by "
+        print("bench.py: the library runs on one GPU only (groups are independent: the path would shard by "
               "partitioning groups over GPUs with replicated weights and no collective). Run with --gpus 1.",
               file=sys.stderr)
         sys.exit(2)

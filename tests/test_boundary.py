@@ -73,7 +73,7 @@ def test_product_never_touches_the_checker():
 
 
 def test_bench_refuses_more_than_one_gpu_and_fails_loudly_without_one():
-    """`bench.py --gpus 2` exits with a message before touching any device (this build runs on one GPU);
+    """`bench.py --gpus 2` exits with a message before touching any device (the library runs on one GPU);
     without a GPU the default run exits non-zero instead of falling back to the CPU."""
     import subprocess
     import sys
