@@ -161,3 +161,18 @@ def test_grpo_loss_matches_the_checker():
     assert (A[:5 * G] == 0).all()                                   # exactly zero, not merely small
     assert np.allclose(A, want_A, rtol=1e-6, atol=1e-7)
     assert abs(loss.item() - want_loss) <= 1e-9 * max(1.0, abs(want_loss))
+
+
+def test_scoring_a_few_hundred_rows_with_split_k_projections():
+    """256 scored rows per call (64 sequences x 4 action tokens): between 129 and 1024 rows the thin projections
+    are split along K, so the score path's final norm has partial sums to add; deep FFN so that the split is real."""
+    shape = synth.ModelShape(1, 256, 4, 2, 64, 16896, 1024)
+    cfg = synth.EpisodeConfig("score-mid", 8, 8, 16, 1, 4, 4, 16, (), 0.3, 0.4)
+    w, prompts, obs_fn, rec = oracle_rollout(shape, cfg, seed=2)
+    mask_fn = lambda t, r: np.ones(cfg.act_len, dtype=bool)
+    ref = oracle_scores(w, cfg, prompts, obs_fn, rec, mask_fn)
+    got, total = gpu_scores(shape, cfg, w, prompts, obs_fn, rec, mask_fn)
+    err = np.abs(got - ref).max()
+    print(f"mid-size scoring: worst per-token error {err:.3e}")
+    assert err <= TOK_TOL
+    assert np.abs(total - ref.sum(axis=(0, 2))).max() <= TOK_TOL * cfg.act_len
