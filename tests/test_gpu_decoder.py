@@ -485,6 +485,22 @@ def test_members_finish_early_and_the_gate_compares_unequal_prefixes():
     assert any(any(n > 0 for n in g["n_done"].values()) for g in rec["gate"].values())
 
 
+def test_members_finish_early_in_a_batch_of_several_hundred_rows():
+    """The same with 48 groups x 8: groups of unequal size while more than 128 rows are live (tiled projections,
+    K splits, the attention's unit maps over hundreds of rows), every logit against the checker."""
+    shape = synth.ModelShape(1, 256, 4, 2, 64, 1024, 512)
+    cfg = synth.EpisodeConfig("finishers-mid", 48, 8, 40, 3, 6, 2, 16, (2,), 0.3, 0.34)
+    rng = np.random.default_rng(3)
+    ends = np.where(rng.random(cfg.n_groups * cfg.G) < 0.3, rng.integers(1, cfg.turns + 1, cfg.n_groups * cfg.G), 10 ** 6)
+    finish_fn = lambda K, r: ends[r] == K
+    rec, stats, worst, mism, near = run_and_compare(shape, cfg, seed=6, finish_fn=finish_fn, tau_H=0.5,
+                                                    kv_pool_bytes=1 << 27)
+    print(f"finishers at {cfg.n_groups * cfg.G} rows: worst |dlogit| = {worst:.3e}, mismatches = {mism}, stats = {stats}")
+    assert worst <= LOGIT_TOL and mism == 0
+    assert stats["seqs_finished"] == sum(len(f) for f in rec["finished"]) > 0
+    assert stats["n_live_seq"] > 128
+
+
 def _episode_properties(cfg, turns, gate_turn):
     """Runs `turns` turns of cfg at the 7B shape on the GPU alone and checks what must hold at any size:
     converging groups (identical prompts and observations) stay bit-identical row by row, have pair-distance
