@@ -11,7 +11,7 @@
  *   - after turn K the mean pairwise prefix edit distance d_K of each group's action
  *     sequences (Section 3.2) is compared with the threshold d_L and a group is cut iff
  *     d_K < d_L (Eq. 2); a cut group stops generating and leaves the batch (Section 3.2,
- *     Appendix C.1).
+ *     paragraph "The gate"; Appendix C.1).
  *
  * Conventions
  *   - Every function returns SR_OK (0) or a negative sr_status; nothing throws or exits.
@@ -50,11 +50,14 @@ typedef enum {
 typedef struct sr_ctx sr_ctx;
 
 /* Decoder shape: pre-norm blocks, RMSNorm, rotate-half RoPE, grouped-query attention,
- * SwiGLU FFN, untied LM head.  head_dim must be 64 or 128; n_q_heads % n_kv_heads == 0. */
+ * SwiGLU FFN.  head_dim must be 64 or 128; n_q_heads % n_kv_heads == 0.  (The paper names the
+ * model family only -- Section 3.1; these fields describe any decoder of that family.) */
 typedef struct {
     int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
     float rms_eps, rope_theta;
-    int32_t qkv_bias; /* 1: q/k/v projections add a bias vector */
+    int32_t qkv_bias;     /* 1: q/k/v projections add a bias vector */
+    int32_t tied_lm_head; /* 1: the LM head is the embedding matrix (sr_weights.lm_head is ignored and may be
+                             NULL); 0: a separate [vocab][hidden] matrix */
 } sr_model_shape;
 
 typedef struct {
@@ -75,6 +78,15 @@ typedef struct {
     float tau_H;             /* 0 = the one-clause gate of Eq. 2; > 0 = sr_gate also retires a group when the
                                 fraction of its members that have finished (sr_finish_sequences) is >= tau_H
                                 (Appendix E, Eq. 3) */
+    int32_t fp32_debug;      /* 1 = debugging build of the path: every activation, the stored keys and values
+                                and the attention probabilities stay in single precision (weights are the same
+                                bf16 values, widened exactly) and the contractions run as plain fp32
+                                multiply-adds.  Paging, copy-on-write, the split of the context and of the
+                                projections' inner dimension, the order in which partial results are added,
+                                token selection, gate and compaction are the ones of the normal path, so a
+                                difference from an exact evaluation beyond single-precision rounding (logits:
+                                1e-4) points at indexing rather than at bf16 operands.  Slow; a KV page takes
+                                twice the bytes, so kv_pool_bytes holds half as many pages. */
 } sr_options;
 
 /* bf16 device pointers; borrowed only for the duration of sr_load_weights. */
@@ -89,7 +101,7 @@ typedef struct {
 
 typedef struct {
     const void *embed;              /* [vocab][hidden] */
-    const void *lm_head;            /* [vocab][hidden] */
+    const void *lm_head;            /* [vocab][hidden]; ignored when tied_lm_head == 1 */
     const void *final_norm;         /* [hidden] */
     const sr_layer_weights *layers; /* HOST array of n_layers entries (of device pointers) */
 } sr_weights;
@@ -141,6 +153,9 @@ int sr_prefill_chunk(sr_ctx *ctx, const int32_t *tokens, int chunk_len, int shar
                      void *stream);
 
 /*
+ * One generation step of every live trajectory (Section 2.2: rollout is token-by-token sampling, one
+ * model call per environment step and trajectory, and is what dominates the wall-clock; Appendix C.1:
+ * the per-step loop over the group's trajectories that the gate interrupts).
  * Decode one token for every live sequence: pick token = forced[r] if forced != NULL, else
  * the library's own choice -- greedy (largest current logit, lowest index on ties) or, with
  * temperature > 0, the sampled token; append it and compute the logits that follow it.
@@ -166,6 +181,9 @@ int sr_decode_step(sr_ctx *ctx, const int32_t *forced, int32_t *out_tokens, void
 int sr_gate(sr_ctx *ctx, int turn, int32_t *out_sums, uint8_t *out_retire, void *stream);
 
 /*
+ * The cut itself (Section 3.2, paragraph "The gate": when the gate fires, every trajectory of the group
+ * that has not ended yet is stopped after step K and the remaining steps are never generated; Appendix
+ * C.1: the cut group is skipped by the trainer).
  * Apply the mask of the preceding sr_gate: rows of retired groups are removed from every
  * per-sequence array (order of survivors kept), their KV pages are released (a shared
  * prompt page returns to the pool when its last holder leaves) and the batch shrinks.
@@ -178,8 +196,9 @@ int sr_retire_and_compact(sr_ctx *ctx, int *host_n_live_groups, void *stream);
 
 /*
  * Take single sequences out of the batch because their trajectory has ended (success or failure
- * reported by the environment) while other members of their group go on (Section 3.3 speaks of
- * the members "still running").  host_done: HOST uint8 [n_live_seq], non-zero = finished.  Call
+ * reported by the environment) while other members of their group go on (Section 3.2, paragraph
+ * "The gate", cuts only the trajectories that have not ended by step K, so some may have; Appendix B
+ * defines the fraction that has, tau_K).  host_done: HOST uint8 [n_live_seq], non-zero = finished.  Call
  * between a turn's last sr_decode_step and the next sr_prefill_chunk: the sequence is recorded as
  * finished after `turn` environment steps.  Its private KV pages are freed and its references to
  * the shared prompt pages dropped; its action prefix is kept, because a later sr_gate still
@@ -187,7 +206,8 @@ int sr_retire_and_compact(sr_ctx *ctx, int *host_n_live_groups, void *stream);
  * lengths, Section 3.2, and the member counts towards tau_K).  A group whose last member
  * finishes leaves the batch without being retired.  Rows keep their order; the sync point is
  * inside (page table and row maps are re-uploaded).  *host_n_live_seq (may be NULL) receives
- * the number of sequences left.  SR_E_STATE: before the first turn or in the middle of one.
+ * the number of sequences left.  SR_E_STATE: before the first turn, in the middle of one, or between
+ * sr_gate and sr_retire_and_compact (the pending mask is indexed by the groups live at the gate).
  * After this call sr_gate writes to out_sums the plain sum of the pair distances.
  */
 int sr_finish_sequences(sr_ctx *ctx, const uint8_t *host_done, int *host_n_live_seq, void *stream);
@@ -206,9 +226,9 @@ int sr_gate_batch(const int32_t *actions, int n_groups, int G, int stride, const
  * exactly like sr_prefill_chunk(..., shared_per_group = 0) -- their K/V are computed and the
  * logits at the chunk's last position are kept -- and adds, for every chunk position t whose
  * action_mask entry is non-zero, log softmax(logits at the position before t)[tokens[t]] to the
- * sequence's running log-likelihood  log p(tau) = sum over action-token positions.  The logits
- * at position t-1 predict the token at position t; the chunk's first token is predicted by the
- * logits the previous prefill / scoring / decode call left, so the context must not be empty
+ * sequence's running log-likelihood  log p(tau) = sum over action-token positions.  A token is scored
+ * by the distribution computed from everything before it, so the chunk's first token is scored by the
+ * logits the previous prefill / scoring / decode call left and the context must not be empty
  * (SR_E_STATE).  Observation tokens are either passed with mask 0 or, cheaper, appended with
  * sr_prefill_chunk, which computes no LM head for them.
  *

@@ -38,16 +38,32 @@ def _cpu_tag() -> str:
     return hashlib.sha1(flags.encode()).hexdigest()[:8]
 
 
-def _lib_path(real: str) -> str:
-    return os.path.join(_HERE, f"libsroracle_{real}_{_cpu_tag()}.so")
+# SRO_SANITIZE=1 in the environment: every load() in this process takes the build instrumented with
+# AddressSanitizer and UndefinedBehaviorSanitizer (the process must have been started with the sanitizer
+# runtime preloaded; tests/test_oracle_sanitized.py does that for a child process).
+_SANITIZE = os.environ.get("SRO_SANITIZE", "") == "1"
 
 
-def build(force: bool = False) -> None:
-    for real in ("double", "float"):
-        out = _lib_path(real)
+def _lib_path(real: str, sanitize: bool = False) -> str:
+    return os.path.join(_HERE, f"libsroracle_{real}{'_san' if sanitize else ''}_{_cpu_tag()}.so")
+
+
+def build(force: bool = False, sanitize: bool = False) -> None:
+    """Compile sr_oracle.c (double and float builds).  sanitize=True: the double build with
+    -fsanitize=address,undefined at -O1 (out-of-bounds accesses, use after free, signed overflow,
+    misaligned or null dereferences abort the process), for the host-side sanitizer leg of the tests."""
+    for real in (("double",) if sanitize else ("double", "float")):
+        out = _lib_path(real, sanitize)
         if force or not os.path.exists(out) or os.path.getmtime(out) < os.path.getmtime(_SRC):
-            subprocess.check_call(["gcc", "-O3", "-march=native", "-fopenmp", "-fPIC", "-shared", "-std=c11",
+            opt = (["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+                    "-fno-sanitize-recover=all"] if sanitize else ["-O3", "-march=native"])
+            subprocess.check_call(["gcc"] + opt + ["-fopenmp", "-fPIC", "-shared", "-std=c11",
                                    f"-DSRO_REAL={real}", "-o", out, _SRC, "-lm"])
+
+
+def sanitizer_runtime() -> str:
+    """Path of the AddressSanitizer runtime that a process loading the sanitized build must preload."""
+    return subprocess.check_output(["gcc", "-print-file-name=libasan.so"], text=True).strip()
 
 
 class _Shape(ctypes.Structure):
@@ -58,8 +74,8 @@ class _Shape(ctypes.Structure):
 
 def load(real: str = "double"):
     if real not in _LIBS:
-        build()
-        L = ctypes.CDLL(_lib_path(real))
+        build(sanitize=_SANITIZE and real == "double")
+        L = ctypes.CDLL(_lib_path(real, _SANITIZE and real == "double"))
         vp, ci, cd = ctypes.c_void_p, ctypes.c_int, ctypes.c_double
         L.sro_lev.restype = ci
         L.sro_lev.argtypes = [vp, ci, vp, ci]
@@ -94,6 +110,10 @@ def load(real: str = "double"):
         L.sro_seq_len.argtypes = [vp]
         L.sro_seq_truncate.restype = None
         L.sro_seq_truncate.argtypes = [vp, ci]
+        L.sro_seq_clone.restype = vp
+        L.sro_seq_clone.argtypes = [vp, vp]
+        L.sro_bf16_round.restype = cd
+        L.sro_bf16_round.argtypes = [cd]
         L.sro_forward_token.restype = ci
         L.sro_forward_token.argtypes = [vp, vp, ctypes.c_int32, vp]
         L.sro_forward.restype = ci
@@ -221,9 +241,14 @@ class Model:
 
 
 class Seq:
-    def __init__(self, model: Model, cap: int):
+    def __init__(self, model: Model, cap: int, _handle=None):
         self.m = model
-        self.h = model.L.sro_seq_new(model.h, cap)
+        self.h = model.L.sro_seq_new(model.h, cap) if _handle is None else _handle
+
+    def clone(self) -> "Seq":
+        """An independent sequence with the same tokens behind it (e.g. the G members of a group after their
+        common prompt: sequences do not interact, so evaluating the prompt once and copying is exact)."""
+        return Seq(self.m, 0, _handle=self.m.L.sro_seq_clone(self.m.h, self.h))
 
     def __del__(self):
         try:
@@ -252,6 +277,11 @@ def set_bf16_contract(on: bool, real: str = "double") -> None:
     """Round activations to bf16 where a bf16 tensor-core implementation must (see sr_oracle.c).
     Off by default; the exact evaluation is the reference, this mode only attributes error."""
     load(real).sro_set_bf16_contract(int(on))
+
+
+def bf16_round(x: float) -> float:
+    """The contract mode's rounding of one value: to single precision, then to the nearest bf16, ties to even."""
+    return float(load().sro_bf16_round(float(x)))
 
 
 def rope_apply(vec, pos: int, theta: float) -> np.ndarray:
@@ -341,7 +371,7 @@ def run_episode(model: Model, prompts, obs_fn, G: int, turns: int, act_len: int,
     n_seq = n_groups * G
     obs0 = obs_fn(0)
     cap = P + turns * (obs0.shape[1] + act_len)
-    seqs = [model.new_seq(cap) for _ in range(n_seq)]
+    seqs = [None] * n_seq
     live = list(range(n_groups))
     actions = np.full((n_seq, turns), -1, dtype=np.int32)
     alive = np.ones(n_seq, dtype=bool)
@@ -349,10 +379,15 @@ def run_episode(model: Model, prompts, obs_fn, G: int, turns: int, act_len: int,
     rec = {"tokens": [], "gaps": [], "logits": [], "live_groups": [], "live_rows": [], "finished": [], "gate": {},
            "decoded_tokens": 0}
 
+    # the prompt is common to the G members of a group and sequences do not interact: evaluate it once per
+    # group and copy the resulting sequence state for the other members
     logits = [None] * n_seq
     for g in live:
+        first = model.new_seq(cap)
+        lg = first.forward(prompts[g])
         for m in range(G):
-            logits[g * G + m] = seqs[g * G + m].forward(prompts[g])
+            seqs[g * G + m] = first if m == 0 else first.clone()
+            logits[g * G + m] = lg if m == 0 else lg.copy()
 
     for turn in range(turns):
         obs = obs0 if turn == 0 else obs_fn(turn)

@@ -314,16 +314,23 @@ typedef struct {
 static int g_contract = 0;
 void sro_set_bf16_contract(int on) { g_contract = on; }
 
-static inline real rb(real x) {
-    if (!g_contract) return x;
+/*
+ * The rounding itself, exported so that tests can pin it: the value is first rounded to
+ * single precision (the accumulators whose contents become bf16 operands are single precision),
+ * then to the nearest bf16 (8 significant bits), ties to the even significand; a carry may
+ * move into the exponent.  Finite inputs only.
+ */
+double sro_bf16_round(double x) {
     float f = (float)x;
     uint32_t u;
     memcpy(&u, &f, 4);
     u += 0x7FFFu + ((u >> 16) & 1u);
     u &= 0xFFFF0000u;
     memcpy(&f, &u, 4);
-    return (real)f;
+    return (double)f;
 }
+
+static inline real rb(real x) { return g_contract ? (real)sro_bf16_round((double)x) : x; }
 
 static inline real bf16_to_real(uint16_t b) {
     uint32_t u = (uint32_t)b << 16;
@@ -375,6 +382,16 @@ void sro_seq_free(sro_seq *q) {
 }
 
 int sro_seq_len(const sro_seq *q) { return q->len; }
+
+/* A second sequence with the same tokens behind it (the flat K/V lists are copied). */
+sro_seq *sro_seq_clone(const sro_model *m, const sro_seq *q) {
+    sro_seq *c = sro_seq_new(m, q->cap);
+    const size_t n = (size_t)m->s.n_layers * q->cap * m->s.n_kv_heads * m->s.head_dim;
+    memcpy(c->k, q->k, n * sizeof(real));
+    memcpy(c->v, q->v, n * sizeof(real));
+    c->len = q->len;
+    return c;
+}
 void sro_seq_truncate(sro_seq *q, int len) { if (len < q->len) q->len = len; }
 
 /* y[n] = W[n][:] . x  (+ bias[n]) */
@@ -432,7 +449,7 @@ int sro_forward_token(const sro_model *m, sro_seq *q, int32_t token, real *logit
     real *proj = (real *)malloc(sizeof(real) * H);
     real *g = (real *)malloc(sizeof(real) * F);
     real *u = (real *)malloc(sizeof(real) * F);
-    real *sc = (real *)malloc(sizeof(real) * (pos + 1));
+    real *sc_all = (real *)malloc(sizeof(real) * (size_t)nq * (pos + 1));   /* one score row per head */
 
     for (int i = 0; i < H; ++i) x[i] = bf16_to_real(m->embed[(size_t)token * H + i]);
 
@@ -454,9 +471,11 @@ int sro_forward_token(const sro_model *m, sro_seq *q, int32_t token, real *logit
         }
 
         const real scale = (real)(1.0 / sqrt((double)d));
-        for (int a = 0; a < nq; ++a) {
+#pragma omp parallel for schedule(static)
+        for (int a = 0; a < nq; ++a) {       /* heads are independent of each other */
             const int kvh = a / rep;
             const real *qa = qv + a * d;
+            real *sc = sc_all + (size_t)a * (pos + 1);
             real mx = -INFINITY;
             for (int t = 0; t <= pos; ++t) {
                 const real *kt = kc + (size_t)t * KD + kvh * d;
@@ -499,7 +518,7 @@ int sro_forward_token(const sro_model *m, sro_seq *q, int32_t token, real *logit
         rmsnorm(x, m->final_norm, (real)s->rms_eps, h, H);
         matvec(m->lm_head, NULL, h, logits, s->vocab, H);
     }
-    free(x); free(h); free(qv); free(att); free(proj); free(g); free(u); free(sc);
+    free(x); free(h); free(qv); free(att); free(proj); free(g); free(u); free(sc_all);
     return 0;
 }
 

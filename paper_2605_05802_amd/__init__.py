@@ -34,14 +34,14 @@ class ModelShape(ctypes.Structure):
     _fields_ = [("n_layers", ctypes.c_int32), ("hidden", ctypes.c_int32), ("n_q_heads", ctypes.c_int32),
                 ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("ffn", ctypes.c_int32),
                 ("vocab", ctypes.c_int32), ("rms_eps", ctypes.c_float), ("rope_theta", ctypes.c_float),
-                ("qkv_bias", ctypes.c_int32)]
+                ("qkv_bias", ctypes.c_int32), ("tied_lm_head", ctypes.c_int32)]
 
 
 class Options(ctypes.Structure):
     _fields_ = [("page_tokens", ctypes.c_int32), ("max_seq_len", ctypes.c_int32), ("max_turns", ctypes.c_int32),
                 ("action_mod", ctypes.c_int32), ("max_prefill_rows", ctypes.c_int32),
                 ("kv_pool_bytes", ctypes.c_uint64), ("temperature", ctypes.c_float),
-                ("sample_seed", ctypes.c_uint64), ("tau_H", ctypes.c_float)]
+                ("sample_seed", ctypes.c_uint64), ("tau_H", ctypes.c_float), ("fp32_debug", ctypes.c_int32)]
 
 
 class LayerWeights(ctypes.Structure):
@@ -169,11 +169,12 @@ class Context:
 
     def __init__(self, shape, n_groups: int, G: int, threshold: float, *, page_tokens=64, max_seq_len=4096,
                  max_turns=32, action_mod=64, max_prefill_rows=0, kv_pool_bytes=1 << 30, temperature=0.0,
-                 sample_seed=0, tau_H=0.0):
+                 sample_seed=0, tau_H=0.0, fp32_debug=False, tied_lm_head=False):
         self.shape = ModelShape(shape.n_layers, shape.hidden, shape.n_q_heads, shape.n_kv_heads, shape.head_dim,
-                                shape.ffn, shape.vocab, shape.rms_eps, shape.rope_theta, int(shape.qkv_bias))
+                                shape.ffn, shape.vocab, shape.rms_eps, shape.rope_theta, int(shape.qkv_bias),
+                                int(tied_lm_head))
         self.opt = Options(page_tokens, max_seq_len, max_turns, action_mod, max_prefill_rows, kv_pool_bytes,
-                           temperature, sample_seed, tau_H)
+                           temperature, sample_seed, tau_H, int(fp32_debug))
         self.G, self.n_groups0, self.vocab, self.max_turns = G, n_groups, shape.vocab, max_turns
         self._h = ctypes.c_void_p()
         _check(lib().sr_init(ctypes.byref(self._h), ctypes.byref(self.shape), n_groups, G, threshold,

@@ -241,6 +241,7 @@ struct MergeArgs {
     int n_phases;
     int n_q, n_kv, d, mt_total;
     uint16_t *out;
+    float *out32;       // non-null: row-major fp32 output instead of `out`
 };
 
 // One block per (query token, query head); thread = head dimension.  The (max, sum) pairs of all
@@ -295,7 +296,8 @@ __global__ __launch_bounds__(128) void attn_merge_kernel(MergeArgs a) {
     }
     for (; i < n_items; ++i) num += po[(size_t)s_row[i] * a.d] * s_w[i];
     const float r = den > 0.f ? num / den : 0.f;
-    a.out[frag_offset(qt, h * a.d + dd, a.mt_total)] = f32_to_bf16(r);
+    if (a.out32) a.out32[((size_t)qt * a.n_q + h) * a.d + dd] = r;
+    else a.out[frag_offset(qt, h * a.d + dd, a.mt_total)] = f32_to_bf16(r);
 }
 
 }  // namespace
@@ -329,7 +331,7 @@ int launch_attention(const AttnArgs &a, const AttnPhase *phases, int n_phases, h
 }
 
 int launch_attn_merge(const AttnArgs &a, const AttnPhase *phases, int n_phases, int n_qtok, uint4 *out,
-                      int mt_total, hipStream_t stream) {
+                      int mt_total, float *out32, hipStream_t stream) {
     if (n_qtok <= 0) return SR_OK;
     if (n_phases < 1 || n_phases > 2) return SR_E_ARG;
     int total = 0;
@@ -340,6 +342,7 @@ int launch_attn_merge(const AttnArgs &a, const AttnPhase *phases, int n_phases, 
     m.n_phases = n_phases;
     m.n_q = a.n_q; m.n_kv = a.n_kv; m.d = a.d; m.mt_total = mt_total;
     m.out = (uint16_t *)out;
+    m.out32 = out32;
     attn_merge_kernel<<<dim3(n_qtok, a.n_q), dim3(128), 0, stream>>>(m);
     SR_HIP(hipGetLastError());
     return SR_OK;

@@ -21,6 +21,7 @@ __device__ __forceinline__ float block_sum_512(float v, float *s_red) {
 
 // x = resid (+ partials) or embedding row; resid <- x (if write_resid); out <- bf16(x * rsqrt(mean(x^2)+eps) * gain)
 // H <= 8192: each thread keeps its (at most 2 x 8) values in registers between the two passes.
+template <bool F32OUT>
 __global__ __launch_bounds__(512) void resid_norm_kernel(NormArgs a) {
     __shared__ float s_red[8];
     const int m = blockIdx.x;
@@ -101,9 +102,15 @@ __global__ __launch_bounds__(512) void resid_norm_kernel(NormArgs a) {
                 y[2 * i] = f[2 * i] * inv * __uint_as_float(gw[i] << 16);
                 y[2 * i + 1] = f[2 * i + 1] * inv * __uint_as_float(gw[i] & 0xFFFF0000u);
             }
-            uint4 o = make_uint4(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]), pack_bf16x2(y[4], y[5]),
-                                 pack_bf16x2(y[6], y[7]));
-            *(uint4 *)((uint16_t *)a.out + frag_offset(m, v * 8, a.mt_total)) = o;
+            if constexpr (F32OUT) {
+                float *dst = a.out32 + (size_t)m * a.H + v * 8;
+                *(f32x4 *)dst = f32x4{y[0], y[1], y[2], y[3]};
+                *(f32x4 *)(dst + 4) = f32x4{y[4], y[5], y[6], y[7]};
+            } else {
+                uint4 o = make_uint4(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]), pack_bf16x2(y[4], y[5]),
+                                     pack_bf16x2(y[6], y[7]));
+                *(uint4 *)((uint16_t *)a.out + frag_offset(m, v * 8, a.mt_total)) = o;
+            }
         }
     }
 }
@@ -276,7 +283,8 @@ __global__ void copy_page_kernel(uint4 *kpool, uint4 *vpool, size_t layer_vec, s
 int launch_resid_norm(const NormArgs &a, hipStream_t stream) {
     if (a.rows_out <= 0) return SR_OK;
     if (a.H % 8 || a.H > 8192) return SR_E_ARG;
-    resid_norm_kernel<<<dim3(a.rows_out), dim3(512), 0, stream>>>(a);
+    if (a.out32) resid_norm_kernel<true><<<dim3(a.rows_out), dim3(512), 0, stream>>>(a);
+    else resid_norm_kernel<false><<<dim3(a.rows_out), dim3(512), 0, stream>>>(a);
     SR_HIP(hipGetLastError());
     return SR_OK;
 }

@@ -107,6 +107,11 @@ struct sr_ctx {
     uint4 *xn = nullptr, *attn_out = nullptr, *act = nullptr;
     uint16_t *q = nullptr;
 
+    // single-precision debugging path (o.fp32_debug): fp32 twins of the activation buffers and of the KV pool
+    bool dbg = false;
+    float *xn32 = nullptr, *attn32 = nullptr, *act32 = nullptr, *q32 = nullptr;
+    float *kpool32 = nullptr, *vpool32 = nullptr;
+
     sr_stats_t st{};
     std::vector<void *> allocs;
 
@@ -265,7 +270,11 @@ int grow_pages(sr_ctx *c, int new_len, bool shared, hipStream_t st) {
                 c->refcnt[np] = 1;
                 c->refcnt[old]--;
                 c->pages[r][idx] = np;
-                SR_TRY(launch_copy_page(c->kpool, c->vpool, c->layer_stride, c->s.n_layers, c->page_elems, old, np, st));
+                if (c->dbg)      // fp32 pages: the same copy over twice as many 16-bit units
+                    SR_TRY(launch_copy_page((uint16_t *)c->kpool32, (uint16_t *)c->vpool32, c->layer_stride * 2,
+                                            c->s.n_layers, c->page_elems * 2, old, np, st));
+                else
+                    SR_TRY(launch_copy_page(c->kpool, c->vpool, c->layer_stride, c->s.n_layers, c->page_elems, old, np, st));
                 c->st.cow_page_copies++;
                 c->pt_dirty = true;
             }
@@ -339,6 +348,17 @@ struct Pass {
     int score_chunk_len, score_unit0;
 };
 
+// K splits of a projection whose partial sums go to c->partials (the same choice on the normal and on the
+// single-precision debugging path)
+int choose_splits(sr_ctx *c, int M, const PackedMat &W, int ld_out, int *splits, size_t *split_stride) {
+    *splits = pick_splits(M, W.N, W.ks);
+    *split_stride = (size_t)round_up(M, 128) * ld_out;
+    if (M > 128)                                     // larger batches may split only as far as the buffer allows
+        while (*splits > 1 && *split_stride * *splits > c->partial_elems) --*splits;
+    if (*split_stride * *splits > c->partial_elems) return SR_E_ARG;
+    return SR_OK;
+}
+
 int gemm(sr_ctx *c, const uint4 *X, const PackedMat &W, int M, GemmEpilogue epi, void *out, int ld_out,
          int *splits_out, hipStream_t st) {
     GemmArgs a{};
@@ -354,14 +374,30 @@ int gemm(sr_ctx *c, const uint4 *X, const PackedMat &W, int M, GemmEpilogue epi,
     a.wide = decode_waves(M, W.N, W.ks, epi == EPI_SWIGLU);
     a.ring = 8;
     if (epi == EPI_F32 && splits_out) {
-        a.splits = pick_splits(M, W.N, W.ks);
-        a.split_stride = (size_t)round_up(M, 128) * ld_out;
-        if (M > 128)                                 // larger batches may split only as far as the buffer allows
-            while (a.splits > 1 && a.split_stride * a.splits > c->partial_elems) --a.splits;
-        if (a.split_stride * a.splits > c->partial_elems) return SR_E_ARG;
+        SR_TRY(choose_splits(c, M, W, ld_out, &a.splits, &a.split_stride));
         *splits_out = a.splits;
     }
     return launch_gemm(a, epi, st);
+}
+
+// The same projection on the single-precision debugging path: X row-major fp32 [M][K]
+int gemm32(sr_ctx *c, const float *X, int K, const PackedMat &W, int M, GemmEpilogue epi, float *out, int ld_out,
+           int *splits_out, hipStream_t st) {
+    DbgGemmArgs a{};
+    a.X = X;
+    a.ldx = K;
+    a.W = W.p;
+    a.M = M;
+    a.N = W.N;
+    a.ks_total = W.ks;
+    a.out = out;
+    a.ld_out = ld_out;
+    a.splits = 1;
+    if (epi == EPI_F32 && splits_out) {
+        SR_TRY(choose_splits(c, M, W, ld_out, &a.splits, &a.split_stride));
+        *splits_out = a.splits;
+    }
+    return launch_dbg_gemm(a, epi, st);
 }
 
 int forward(sr_ctx *c, const Pass &p, hipStream_t st) {
@@ -458,14 +494,21 @@ int forward(sr_ctx *c, const Pass &p, hipStream_t st) {
     }
     if (part_rows > c->part_rows_cap) return SR_E_NOMEM;
     // one partial result per query row: the attention kernel writes the merged output itself
-    aa.direct_out = n_ph == 1 && ph[0].n_splits == 1 ? (uint16_t *)c->attn_out : nullptr;
+    const bool direct = n_ph == 1 && ph[0].n_splits == 1;
+    const bool dbg = c->dbg;
+    const int qd = s.n_q_heads * s.head_dim;
+    aa.direct_out = direct && !dbg ? (uint16_t *)c->attn_out : nullptr;
     aa.out_mt_total = c->mt_total;
+    DbgAttnArgs da{};
+    da.q32 = c->q32;
+    da.direct_out32 = direct && dbg ? c->attn32 : nullptr;
 
     for (int l = 0; l < s.n_layers; ++l) {
         const LayerW &w = c->L[l];
         NormArgs na{};
         na.resid = c->resid;
         na.out = c->xn;
+        na.out32 = dbg ? c->xn32 : nullptr;
         na.rows_out = M;
         na.src_dup = 1;
         na.src_stride = 1;
@@ -489,8 +532,10 @@ int forward(sr_ctx *c, const Pass &p, hipStream_t st) {
         SR_TRY(timed(c, SR_KC_NORM, st, [&] { return launch_resid_norm(na, st); }));
 
         int sp = 1;
-        SR_TRY(timed(c, SR_KC_GEMM_QKV, st,
-                     [&] { return gemm(c, c->xn, w.qkv, M, EPI_F32, c->partials, c->qkv_cols, &sp, st); }));
+        SR_TRY(timed(c, SR_KC_GEMM_QKV, st, [&] {
+            return dbg ? gemm32(c, c->xn32, H, w.qkv, M, EPI_F32, c->partials, c->qkv_cols, &sp, st)
+                       : gemm(c, c->xn, w.qkv, M, EPI_F32, c->partials, c->qkv_cols, &sp, st);
+        }));
         QkvPostArgs qa{};
         qa.partials = c->partials;
         qa.n_partials = sp;
@@ -514,19 +559,35 @@ int forward(sr_ctx *c, const Pass &p, hipStream_t st) {
         qa.n_kv = s.n_kv_heads;
         qa.d = s.head_dim;
         qa.page_tokens = c->o.page_tokens;
-        SR_TRY(timed(c, SR_KC_QKV_POST, st, [&] { return launch_qkv_post(qa, st); }));
-
-        aa.kpool = qa.kpool;
-        aa.vpool = qa.vpool;
-        SR_TRY(timed(c, p.decode ? SR_KC_ATTN_DECODE : SR_KC_ATTN_PREFILL, st,
-                     [&] { return launch_attention(aa, ph, n_ph, st); }));
-        if (!aa.direct_out) {
-            SR_TRY(timed(c, SR_KC_ATTN_MERGE, st,
-                         [&] { return launch_attn_merge(aa, ph, n_ph, M, c->attn_out, c->mt_total, st); }));
+        if (dbg) {
+            DbgQkvPostArgs dq{};
+            dq.base = qa;
+            dq.q32 = c->q32;
+            dq.kpool32 = c->kpool32 + (size_t)l * c->layer_stride;
+            dq.vpool32 = c->vpool32 + (size_t)l * c->layer_stride;
+            SR_TRY(timed(c, SR_KC_QKV_POST, st, [&] { return launch_dbg_qkv_post(dq, st); }));
+            da.base = aa;
+            da.kpool32 = dq.kpool32;
+            da.vpool32 = dq.vpool32;
+            SR_TRY(timed(c, p.decode ? SR_KC_ATTN_DECODE : SR_KC_ATTN_PREFILL, st,
+                         [&] { return launch_dbg_attention(da, ph, n_ph, st); }));
+        } else {
+            SR_TRY(timed(c, SR_KC_QKV_POST, st, [&] { return launch_qkv_post(qa, st); }));
+            aa.kpool = qa.kpool;
+            aa.vpool = qa.vpool;
+            SR_TRY(timed(c, p.decode ? SR_KC_ATTN_DECODE : SR_KC_ATTN_PREFILL, st,
+                         [&] { return launch_attention(aa, ph, n_ph, st); }));
+        }
+        if (!direct) {
+            SR_TRY(timed(c, SR_KC_ATTN_MERGE, st, [&] {
+                return launch_attn_merge(aa, ph, n_ph, M, c->attn_out, c->mt_total, dbg ? c->attn32 : nullptr, st);
+            }));
         }
 
-        SR_TRY(timed(c, SR_KC_GEMM_O, st,
-                     [&] { return gemm(c, c->attn_out, w.o, M, EPI_F32, c->partials, H, &sp, st); }));
+        SR_TRY(timed(c, SR_KC_GEMM_O, st, [&] {
+            return dbg ? gemm32(c, c->attn32, qd, w.o, M, EPI_F32, c->partials, H, &sp, st)
+                       : gemm(c, c->attn_out, w.o, M, EPI_F32, c->partials, H, &sp, st);
+        }));
         na.embed = nullptr;
         na.tokens = nullptr;
         na.partials = c->partials;
@@ -535,10 +596,14 @@ int forward(sr_ctx *c, const Pass &p, hipStream_t st) {
         na.gain = w.norm2;
         SR_TRY(timed(c, SR_KC_NORM, st, [&] { return launch_resid_norm(na, st); }));
 
-        SR_TRY(timed(c, SR_KC_GEMM_GATE_UP, st,
-                     [&] { return gemm(c, c->xn, w.gu, M, EPI_SWIGLU, c->act, c->ks_f * 32, nullptr, st); }));
-        SR_TRY(timed(c, SR_KC_GEMM_DOWN, st,
-                     [&] { return gemm(c, c->act, w.down, M, EPI_F32, c->partials, H, &sp, st); }));
+        SR_TRY(timed(c, SR_KC_GEMM_GATE_UP, st, [&] {
+            return dbg ? gemm32(c, c->xn32, H, w.gu, M, EPI_SWIGLU, c->act32, s.ffn, nullptr, st)
+                       : gemm(c, c->xn, w.gu, M, EPI_SWIGLU, c->act, c->ks_f * 32, nullptr, st);
+        }));
+        SR_TRY(timed(c, SR_KC_GEMM_DOWN, st, [&] {
+            return dbg ? gemm32(c, c->act32, s.ffn, w.down, M, EPI_F32, c->partials, H, &sp, st)
+                       : gemm(c, c->act, w.down, M, EPI_F32, c->partials, H, &sp, st);
+        }));
         n_part = sp;
         part_stride = (size_t)round_up(M, 128) * H;
     }
@@ -553,6 +618,7 @@ int forward(sr_ctx *c, const Pass &p, hipStream_t st) {
         na.partial_stride = part_stride;
         na.gain = c->final_norm;
         na.out = c->xn;
+        na.out32 = dbg ? c->xn32 : nullptr;
         na.rows_out = M;
         na.src_dup = 1;
         na.src_stride = 1;
@@ -565,8 +631,11 @@ int forward(sr_ctx *c, const Pass &p, hipStream_t st) {
         for (int r0 = 0; r0 < M; r0 += kScoreRows) {
             const int blk = M - r0 < kScoreRows ? M - r0 : kScoreRows;
             const uint4 *x = c->xn + (size_t)(r0 / 16) * 64;      // row tile r0 / 16 of every k-step
-            SR_TRY(timed(c, SR_KC_GEMM_LM_HEAD, st,
-                         [&] { return gemm(c, x, c->lm, blk, EPI_F32, c->score_logits, s.vocab, nullptr, st); }));
+            SR_TRY(timed(c, SR_KC_GEMM_LM_HEAD, st, [&] {
+                return dbg ? gemm32(c, c->xn32 + (size_t)r0 * H, H, c->lm, blk, EPI_F32, c->score_logits, s.vocab,
+                                    nullptr, st)
+                           : gemm(c, x, c->lm, blk, EPI_F32, c->score_logits, s.vocab, nullptr, st);
+            }));
             LogprobArgs la{};
             la.logits = c->score_logits;
             la.vocab = s.vocab;
@@ -589,6 +658,7 @@ int forward(sr_ctx *c, const Pass &p, hipStream_t st) {
         na.partial_stride = part_stride;
         na.gain = c->final_norm;
         na.out = c->xn;
+        na.out32 = dbg ? c->xn32 : nullptr;
         na.rows_out = p.n_units * p.logit_dup;
         na.src_dup = p.logit_dup;
         na.src_stride = p.chunk;
@@ -599,8 +669,10 @@ int forward(sr_ctx *c, const Pass &p, hipStream_t st) {
         na.eps = s.rms_eps;
         SR_TRY(timed(c, SR_KC_NORM, st, [&] { return launch_resid_norm(na, st); }));
         float *dst = c->d_logits[c->cur] + (size_t)p.logit_row0 * s.vocab;
-        SR_TRY(timed(c, SR_KC_GEMM_LM_HEAD, st,
-                     [&] { return gemm(c, c->xn, c->lm, na.rows_out, EPI_F32, dst, s.vocab, nullptr, st); }));
+        SR_TRY(timed(c, SR_KC_GEMM_LM_HEAD, st, [&] {
+            return dbg ? gemm32(c, c->xn32, H, c->lm, na.rows_out, EPI_F32, dst, s.vocab, nullptr, st)
+                       : gemm(c, c->xn, c->lm, na.rows_out, EPI_F32, dst, s.vocab, nullptr, st);
+        }));
     }
     return SR_OK;
 }
@@ -668,17 +740,26 @@ static int init_impl(sr_ctx *c) {
     }
 
     // KV pool: [layer][page][kv head][32-token block][32*d], K and V separately
+    c->dbg = o.fp32_debug != 0;
     c->page_elems = (size_t)s.n_kv_heads * o.page_tokens * d;
-    const size_t page_bytes_all = c->page_elems * 2 * s.n_layers * 2;
+    const size_t elem_bytes = c->dbg ? 4 : 2;
+    const size_t page_bytes_all = c->page_elems * elem_bytes * s.n_layers * 2;
     c->n_pages = (int)(o.kv_pool_bytes / page_bytes_all);
     c->max_pages = ceil_div(o.max_seq_len, o.page_tokens);
     if (c->n_pages < 1) return SR_E_ARG;
     c->layer_stride = c->page_elems * c->n_pages;
-    SR_TRY(dev_alloc(c, &c->kpool, c->layer_stride * s.n_layers));
-    SR_TRY(dev_alloc(c, &c->vpool, c->layer_stride * s.n_layers));
-    // masked probabilities multiply V entries that were never written: they must be finite
-    SR_HIP(hipMemset(c->kpool, 0, c->layer_stride * s.n_layers * 2));
-    SR_HIP(hipMemset(c->vpool, 0, c->layer_stride * s.n_layers * 2));
+    if (c->dbg) {
+        SR_TRY(dev_alloc(c, &c->kpool32, c->layer_stride * s.n_layers));
+        SR_TRY(dev_alloc(c, &c->vpool32, c->layer_stride * s.n_layers));
+        SR_HIP(hipMemset(c->kpool32, 0, c->layer_stride * s.n_layers * 4));
+        SR_HIP(hipMemset(c->vpool32, 0, c->layer_stride * s.n_layers * 4));
+    } else {
+        SR_TRY(dev_alloc(c, &c->kpool, c->layer_stride * s.n_layers));
+        SR_TRY(dev_alloc(c, &c->vpool, c->layer_stride * s.n_layers));
+        // masked probabilities multiply V entries that were never written: they must be finite
+        SR_HIP(hipMemset(c->kpool, 0, c->layer_stride * s.n_layers * 2));
+        SR_HIP(hipMemset(c->vpool, 0, c->layer_stride * s.n_layers * 2));
+    }
     c->refcnt.assign(c->n_pages, 0);
     c->free_list.resize(c->n_pages);
     for (int i = 0; i < c->n_pages; ++i) c->free_list[i] = c->n_pages - 1 - i;
@@ -744,6 +825,12 @@ static int init_impl(sr_ctx *c) {
     SR_HIP(hipMemset(c->attn_out, 0, R * (size_t)(c->ks_q * 32) * 2));
     SR_HIP(hipMemset(c->act, 0, R * (size_t)(c->ks_f * 32) * 2));
     SR_TRY(dev_alloc(c, &c->q, R * (size_t)s.n_q_heads * d));
+    if (c->dbg) {
+        SR_TRY(dev_alloc(c, &c->xn32, R * (size_t)s.hidden));
+        SR_TRY(dev_alloc(c, &c->attn32, R * (size_t)s.n_q_heads * d));
+        SR_TRY(dev_alloc(c, &c->act32, R * (size_t)s.ffn));
+        SR_TRY(dev_alloc(c, &c->q32, R * (size_t)s.n_q_heads * d));
+    }
     SR_TRY(dev_alloc(c, &c->part_o, c->part_rows_cap * d));
     SR_TRY(dev_alloc(c, &c->part_ml, c->part_rows_cap * 2));
     SR_HIP(hipDeviceSynchronize());
@@ -762,7 +849,8 @@ int sr_init(sr_ctx **out, const sr_model_shape *shape, int n_groups, int G, doub
         return SR_E_ARG;
     if ((opt->page_tokens != 32 && opt->page_tokens != 64 && opt->page_tokens != 128) || opt->max_seq_len < 1 ||
         opt->max_turns < 1 || opt->max_turns > 32 || opt->action_mod < 0 || opt->max_prefill_rows < 0 ||
-        !(opt->temperature >= 0.f) || !(opt->tau_H >= 0.f) || opt->tau_H > 4.f)
+        !(opt->temperature >= 0.f) || !(opt->tau_H >= 0.f) || opt->tau_H > 4.f ||
+        (opt->fp32_debug != 0 && opt->fp32_debug != 1) || (s.tied_lm_head != 0 && s.tied_lm_head != 1))
         return SR_E_ARG;
     sr_ctx *c = new sr_ctx();
     c->s = s;
@@ -780,7 +868,8 @@ int sr_init(sr_ctx **out, const sr_model_shape *shape, int n_groups, int G, doub
 }
 
 int sr_load_weights(sr_ctx *c, const sr_weights *w, void *stream) {
-    if (!c || !w || !w->embed || !w->lm_head || !w->final_norm || !w->layers) return SR_E_ARG;
+    if (!c || !w || !w->embed || !w->final_norm || !w->layers) return SR_E_ARG;
+    if (!c->s.tied_lm_head && !w->lm_head) return SR_E_ARG;
     if (c->weights_loaded) return SR_E_STATE;
     hipStream_t st = (hipStream_t)stream;
     const sr_model_shape &s = c->s;
@@ -793,7 +882,9 @@ int sr_load_weights(sr_ctx *c, const sr_weights *w, void *stream) {
     SR_TRY(copy_vec(c, &c->embed, w->embed, (size_t)s.vocab * H, st));
     SR_TRY(copy_vec(c, &c->final_norm, w->final_norm, H, st));
     SR_TRY(alloc_packed(c, &c->lm, s.vocab, H, st));
-    SR_TRY(launch_pack_rows((const uint16_t *)w->lm_head, s.vocab, H, c->lm.p, c->lm.ks, 0, 0, 0, st));
+    // tied: the LM head is the embedding matrix, packed like any other projection
+    SR_TRY(launch_pack_rows((const uint16_t *)(s.tied_lm_head ? w->embed : w->lm_head), s.vocab, H, c->lm.p, c->lm.ks,
+                            0, 0, 0, st));
     c->L.resize(s.n_layers);
     for (int l = 0; l < s.n_layers; ++l) {
         const sr_layer_weights &x = w->layers[l];
@@ -1101,6 +1192,9 @@ int sr_retire_and_compact(sr_ctx *c, int *host_n_live_groups, void *stream) {
 int sr_finish_sequences(sr_ctx *c, const uint8_t *host_done, int *host_n_live_seq, void *stream) {
     if (!c || !host_done) return SR_E_ARG;
     if (c->turn < 1 || c->first_decode_of_turn) return SR_E_STATE;    // between a turn's decode and the next prefill
+    // the mask of a gate that has not been applied yet is indexed by the groups live at that gate; dropping a
+    // whole group now would shift it onto the wrong groups
+    if (c->gate_pending) return SR_E_STATE;
     hipStream_t st = (hipStream_t)stream;
     const int n = c->n_rows;
     std::vector<char> drop(n, 0);

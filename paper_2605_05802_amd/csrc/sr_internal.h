@@ -144,6 +144,7 @@ struct NormArgs {
     const uint16_t *embed;
     const uint16_t *gain;    // [H] bf16
     uint4 *out;              // fragment-major bf16 [rows_out][H]
+    float *out32;            // non-null (single-precision debugging path): row-major fp32 [rows_out][H] instead of `out`
     int rows_out;            // rows normalised (grid size)
     int src_dup, src_stride, src_off;  // source row of output row m: (m / src_dup) * src_stride + src_off
     int write_resid;         // 0: leave resid untouched (several output rows may share one source row)
@@ -219,10 +220,44 @@ struct AttnArgs {
 // One launch over one or two phases (same rt); phases whose token range is empty contribute no work.
 int launch_attention(const AttnArgs &a, const AttnPhase *phases, int n_phases, hipStream_t stream);
 
-// Merge the partial results of up to two phases into out (fragment-major bf16 [query tokens][n_q*d]).
+// Merge the partial results of up to two phases into out (fragment-major bf16 [query tokens][n_q*d]) or, when
+// out32 is non-null (single-precision debugging path), into out32 (row-major fp32, same shape).
 // Query token qt belongs to unit qt / q_per_unit of each phase.
 int launch_attn_merge(const AttnArgs &a, const AttnPhase *phases, int n_phases, int n_qtok, uint4 *out,
-                      int mt_total, hipStream_t stream);
+                      int mt_total, float *out32, hipStream_t stream);
+
+// ---------------------------------------------------------------------------------------------
+// single-precision debugging path (sr_options.fp32_debug): same work decomposition, plain fp32 arithmetic
+// ---------------------------------------------------------------------------------------------
+// Y = X W^T with X row-major fp32 [M][K] and W the packed bf16 matrix of the normal path (widened exactly).
+// K splits cover the same k-step ranges as the normal path's split-K; EPI_F32 writes [split][M][ld_out] fp32,
+// EPI_SWIGLU writes silu(gate) * up as row-major fp32 [M][ld_out] (ld_out = ffn; splits must be 1).
+struct DbgGemmArgs {
+    const float *X;
+    int ldx;                 // = K, the valid inner dimension
+    const uint16_t *W;
+    int M, N, ks_total, splits;
+    float *out;
+    int ld_out;
+    size_t split_stride;
+};
+int launch_dbg_gemm(const DbgGemmArgs &a, GemmEpilogue epi, hipStream_t stream);
+
+// qkv_post with fp32 outputs: q_out [rows][n_q][d] fp32; K and V pages [page][kv head][page_tokens][d] fp32.
+struct DbgQkvPostArgs {
+    QkvPostArgs base;        // q_out, kpool, vpool of `base` are unused
+    float *q32, *kpool32, *vpool32;
+};
+int launch_dbg_qkv_post(const DbgQkvPostArgs &a, hipStream_t stream);
+
+// Attention over fp32 pages with the phases, work items and partial-result format of launch_attention.
+// direct_out32 (row-major fp32 [query tokens][n_q*d]) plays the role of AttnArgs::direct_out.
+struct DbgAttnArgs {
+    AttnArgs base;           // q, kpool, vpool, direct_out of `base` are unused
+    const float *q32, *kpool32, *vpool32;
+    float *direct_out32;
+};
+int launch_dbg_attention(const DbgAttnArgs &a, const AttnPhase *phases, int n_phases, hipStream_t stream);
 
 // ---------------------------------------------------------------------------------------------
 // teacher-forced scoring

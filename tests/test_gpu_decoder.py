@@ -16,7 +16,8 @@ from paper_2605_05802_amd.runner import load_host_weights
 
 pytestmark = pytest.mark.gpu
 
-LOGIT_TOL = 3e-2
+LOGIT_TOL = 3e-2     # bf16 path against the exact evaluation (see `tolerance` for shapes where bf16 itself costs more)
+FP32_TOL = 1e-4      # single-precision debugging path against the exact evaluation
 GAP_RULE = 1e-2
 
 
@@ -24,24 +25,70 @@ def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
+def contract_replay(w, cfg, rec, prompts, obs_fn, rows):
+    """The checker's bf16-contract evaluation (activations rounded to bf16 where matrix-core operands must be,
+    everything else exact) of the sequences in `rows`, fed the tokens of the exact episode `rec`: logits at the
+    points where the episode recorded them, {(turn, step): {row: logits}}."""
+    model = oracle.Model(w)
+    cap = cfg.prompt_len + cfg.turns * (cfg.obs_len + cfg.act_len)
+    out = {}
+    oracle.set_bf16_contract(True)
+    try:
+        for r in rows:
+            seq = model.new_seq(cap)
+            seq.forward(prompts[r // cfg.G], want_logits=False)
+            for turn in range(cfg.turns):
+                if r not in rec["live_rows"][turn]:
+                    break
+                lg = seq.forward(obs_fn(turn)[r])
+                for a in range(cfg.act_len):
+                    out.setdefault((turn, a), {})[r] = lg
+                    lg = seq.forward([rec["tokens"][turn][a, r]])
+    finally:
+        oracle.set_bf16_contract(False)
+    return out
+
+
+def tolerance(contract_err):
+    """The one rule for logits on the bf16 path: within 3e-2 of the exact evaluation, or -- where rounding the
+    matrix-core operands to bf16 alone already costs more than half of that -- within twice what it costs, as
+    measured by the checker's contract mode on the same inputs (the path rounds the same operands, but of values
+    that differ in the last fp32 bits, so its error is the contract mode's plus one more of the same size)."""
+    return max(LOGIT_TOL, 2.0 * contract_err)
+
+
+def gap_rule(tol):
+    """Greedy tokens may differ only where the exact top-2 gap is below 1e-2 -- a third of the 3e-2 logit bound; where
+    the logit bound is the derived one, the gap rule keeps that ratio."""
+    return GAP_RULE * tol / LOGIT_TOL
+
+
 def run_and_compare(shape, cfg, seed, *, page_tokens=32, max_prefill_rows=0, sigma=0.02, weights=None,
-                    kv_pool_bytes=1 << 28, finish_fn=None, tau_H=None):
-    """Runs the whole gated episode on both sides; returns (rec, stats, worst logit error, token mismatches)."""
+                    kv_pool_bytes=1 << 28, finish_fn=None, tau_H=None, fp32_debug=False, contract_rows=None,
+                    rec=None, info=None):
+    """Runs the whole gated episode on both sides; returns (rec, stats, worst logit error, token mismatches,
+    near ties).  contract_rows: also evaluate these sequences in the checker's contract mode and report, in
+    `info`, its largest distance from the exact logits (`contract_max`, `contract_mean`) next to the GPU's
+    (`gpu_mean`).  rec: reuse the checker's record of an earlier call with the same inputs."""
     w = weights if weights is not None else synth.make_weights(shape, seed=0, sigma=sigma)
     conv = synth.converging_groups(cfg, seed)
     prompts = synth.prompts(cfg, shape.vocab, seed)
     obs_fn = lambda t: synth.observations(cfg, shape.vocab, seed, t, conv)
-    rec = oracle.run_episode(oracle.Model(w), prompts, obs_fn, cfg.G, cfg.turns, cfg.act_len, cfg.action_mod,
-                             cfg.gate_turns, cfg.threshold, keep_logits=True, finish_fn=finish_fn, tau_H=tau_H)
+    if rec is None:
+        rec = oracle.run_episode(oracle.Model(w), prompts, obs_fn, cfg.G, cfg.turns, cfg.act_len, cfg.action_mod,
+                                 cfg.gate_turns, cfg.threshold, keep_logits=True, finish_fn=finish_fn, tau_H=tau_H)
+    con = contract_replay(w, cfg, rec, prompts, obs_fn, contract_rows) if contract_rows else {}
 
     max_len = cfg.prompt_len + cfg.turns * (cfg.obs_len + cfg.act_len)
     ctx = sr.Context(shape, cfg.n_groups, cfg.G, cfg.threshold, page_tokens=page_tokens, max_seq_len=max_len,
                      max_turns=max(cfg.turns, 1), action_mod=cfg.action_mod, max_prefill_rows=max_prefill_rows,
-                     kv_pool_bytes=kv_pool_bytes, tau_H=tau_H or 0.0)
+                     kv_pool_bytes=kv_pool_bytes, tau_H=tau_H or 0.0, fp32_debug=fp32_debug)
     load_host_weights(ctx, w)
     ctx.sr_prefill_chunk(dev(prompts), True)
 
     worst, mismatches, near_ties = 0.0, 0, 0
+    con_max = con_mean = gpu_mean = 0.0
+    mismatch_gaps = []
     V = shape.vocab
     for turn in range(cfg.turns):
         live = rec["live_groups"][turn]
@@ -59,7 +106,12 @@ def run_and_compare(shape, cfg, seed, *, page_tokens=32, max_prefill_rows=0, sig
             got = logits.cpu().numpy().astype(np.float64)
             ref = np.stack([rec["logits"][turn][a][r] for r in rows])
             assert np.all(np.isfinite(got))
-            worst = max(worst, float(np.abs(got - ref).max()))
+            err = np.abs(got - ref)
+            worst = max(worst, float(err.max()))
+            gpu_mean = max(gpu_mean, float(err.mean(axis=1).max()))
+            for r, lg in con.get((turn, a), {}).items():
+                d = np.abs(lg - rec["logits"][turn][a][r])
+                con_max, con_mean = max(con_max, float(d.max())), max(con_mean, float(d.mean()))
             forced = rec["tokens"][turn][a, rows]
             ctx.sr_decode_step(dev(forced), greedy)
             torch.cuda.synchronize()
@@ -67,6 +119,7 @@ def run_and_compare(shape, cfg, seed, *, page_tokens=32, max_prefill_rows=0, sig
             gaps = rec["gaps"][turn][a, rows]
             bad = (g != forced) & (gaps >= GAP_RULE)
             mismatches += int(bad.sum())
+            mismatch_gaps += [float(x) for x in gaps[bad]]
             near_ties += int(((g != forced) & (gaps < GAP_RULE)).sum())
         K = turn + 1
         acts = torch.empty((len(rows), max(cfg.turns, 1)), dtype=torch.int32, device="cuda")
@@ -89,6 +142,8 @@ def run_and_compare(shape, cfg, seed, *, page_tokens=32, max_prefill_rows=0, sig
     stats = ctx.sr_stats()
     assert stats["decoded_tokens"] == rec["decoded_tokens"]
     ctx.close()
+    if info is not None:
+        info.update(contract_max=con_max, contract_mean=con_mean, gpu_mean=gpu_mean, mismatch_gaps=mismatch_gaps)
     return rec, stats, worst, mismatches, near_ties
 
 
@@ -112,14 +167,30 @@ def test_tiny_config_episode():
 
 
 def test_larger_scale_weights_and_head_dim_128():
-    """head_dim 128, 7 query heads per kv head (the 7B grouping), larger weight scale so that attention
-    is far from uniform; sub-chunked prefill (row cap below one chunk of the whole batch)."""
+    """head_dim 128, 7 query heads per kv head (the 7B grouping), weight scale 0.05 so that attention is far from
+    uniform (logits of order 10 instead of order 1); sub-chunked prefill (row cap below one chunk of the whole
+    batch).  At this scale rounding the operands to bf16 alone moves the logits by more than 1.5e-2, so the bound
+    is the general rule: twice the contract mode's own distance from the exact logits, every row evaluated in
+    both modes.  The single-precision path on the same inputs must agree to 1e-4: what is left on the bf16 path
+    is rounding, not indexing."""
     shape = synth.ModelShape(2, 512, 14, 2, 128, 1024, 2048)
     cfg = synth.EpisodeConfig("gqa7", 3, 8, 96, 3, 40, 4, 64, (2,), 0.3, 0.34)
+    info = {}
     rec, stats, worst, mism, near = run_and_compare(shape, cfg, seed=3, page_tokens=64, max_prefill_rows=256,
-                                                     sigma=0.03)
-    print(f"gqa7: worst |dlogit| = {worst:.3e}, mismatches = {mism}, near ties = {near}")
-    assert worst <= LOGIT_TOL and mism == 0
+                                                     sigma=0.05, contract_rows=list(range(24)), info=info)
+    tol = tolerance(info["contract_max"])
+    print(f"gqa7 sigma 0.05: worst |dlogit| = {worst:.3e} (mean {info['gpu_mean']:.3e}); contract mode "
+          f"{info['contract_max']:.3e} (mean {info['contract_mean']:.3e}); bound {tol:.3e}; mismatches = {mism}, "
+          f"near ties = {near}, gaps at the mismatches = {info['mismatch_gaps']}")
+    assert worst <= tol and info["gpu_mean"] <= 2.0 * info["contract_mean"]
+    assert all(g < gap_rule(tol) for g in info["mismatch_gaps"])
+    _, _, worst32, mism32, _ = run_and_compare(shape, cfg, seed=3, page_tokens=64, max_prefill_rows=256, sigma=0.05,
+                                               fp32_debug=True, rec=rec)
+    print(f"gqa7 sigma 0.05, single precision: worst |dlogit| = {worst32:.3e}")
+    assert worst32 <= FP32_TOL and mism32 == 0
+    # the original, smaller weight scale stays under the plain 3e-2
+    _, _, worst03, mism03, _ = run_and_compare(shape, cfg, seed=3, page_tokens=64, max_prefill_rows=256, sigma=0.03)
+    assert worst03 <= LOGIT_TOL and mism03 == 0
 
 
 def test_prompt_not_page_aligned_copies_on_write():
@@ -373,7 +444,7 @@ def test_7b_shape_sampled_sequences():
     print(f"7B shape: GPU vs exact max {gpu_max:.3e} mean {gpu_mean:.3e}; bf16 contract vs exact max {con_max:.3e} "
           f"mean {con_mean:.3e}; token mismatches {mism}")
     ctx.close()
-    assert gpu_max <= 2.0 * con_max and gpu_mean <= 2.0 * con_mean and mism == 0
+    assert gpu_max <= tolerance(con_max) and gpu_mean <= 2.0 * con_mean and mism == 0
 
 
 def test_group_size_16_with_two_gate_turns():
@@ -501,12 +572,146 @@ def test_members_finish_early_in_a_batch_of_several_hundred_rows():
     assert stats["n_live_seq"] > 128
 
 
-def _episode_properties(cfg, turns, gate_turn):
-    """Runs `turns` turns of cfg at the 7B shape on the GPU alone and checks what must hold at any size:
-    converging groups (identical prompts and observations) stay bit-identical row by row, have pair-distance
-    sum 0 and are retired; token and page accounting follow the closed forms."""
+@pytest.mark.parametrize("case", ["tiny", "cow", "g16", "edge", "finishers", "mid"])
+def test_single_precision_debug_path(case):
+    """sr_options.fp32_debug: fp32 activations, fp32 K/V pages and plain multiply-adds behind the same paging,
+    splits, merges and compaction.  Logits within 1e-4 of the exact evaluation, tokens identical under the gap
+    rule, gate and live maps exact -- on an episode with a gate, on a prompt that ends inside a page (copy on
+    write of fp32 pages), on G = 16 with two gates, on widths that do not fill a tile, on groups that lose single
+    members, and on a batch of several hundred rows (tiled projections with K splits)."""
+    kw = dict(fp32_debug=True)
+    if case == "tiny":
+        shape, cfg, seed = synth.TINY, synth.TINY_EPISODE, 0
+    elif case == "cow":
+        shape, cfg, seed = synth.ModelShape(1, 128, 4, 2, 64, 256, 256), synth.EpisodeConfig("cow", 2, 4, 40, 2, 5, 3, 16, (), 0.3, 0.5), 5
+        kw.update(sigma=0.08)
+    elif case == "g16":
+        shape, cfg, seed = synth.ModelShape(2, 256, 4, 2, 64, 512, 512), synth.EpisodeConfig("g16", 5, 16, 64, 5, 12, 3, 8, (2, 4), 0.25, 0.4), 21
+    elif case == "edge":
+        shape, cfg, seed = synth.ModelShape(2, 384, 12, 4, 128, 1040, 2064), synth.EpisodeConfig("edge", 3, 7, 37, 2, 5, 3, 16, (1,), 0.3, 0.4), 11
+        kw.update(page_tokens=128, kv_pool_bytes=1 << 27)
+    elif case == "finishers":
+        shape, cfg, seed = synth.TINY, synth.EpisodeConfig("finishers", 6, 8, 64, 6, 16, 4, 16, (2, 4), 0.3, 0.34), 2
+        rng = np.random.default_rng(7)
+        ends = np.where(rng.random(48) < 0.45, rng.integers(1, 7, 48), 10 ** 6)
+        kw.update(finish_fn=lambda K, r: ends[r] == K, tau_H=0.5)
+    else:
+        shape, cfg, seed = synth.ModelShape(1, 256, 4, 2, 64, 16896, 1024), synth.EpisodeConfig("mid", 64, 8, 16, 2, 2, 2, 64, (1,), 0.3, 0.4), 4
+    rec, stats, worst, mism, near = run_and_compare(shape, cfg, seed, **kw)
+    print(f"single precision, {case}: worst |dlogit| = {worst:.3e}, mismatches = {mism}, near ties = {near}")
+    assert worst <= FP32_TOL and mism == 0
+    if case == "cow":
+        assert stats["cow_page_copies"] == 2 * 3
+
+
+def test_full_width_long_shared_prompt_every_row():
+    """The benchmark's attention regime at the full model width, every live row against the checker: hidden 3584,
+    28 query / 4 kv heads of 128, FFN 18944, vocabulary 152064 (two layers, so that the CPU can follow), G = 8,
+    64-token pages, a shared prompt of 1100 tokens that ends inside a page -- 1088 shared tokens in five splits
+    with two members per work item, the last 12 prompt tokens copied on write -- and two turns of 124 observation
+    + 4 decoded tokens, so that the private context (268 tokens at the end) runs in up to three splits.  The
+    single-precision path must agree with the exact evaluation to 1e-4 (indexing, paging, splits and merges are
+    right); the bf16 path is held to the general rule, with the contract mode evaluated on four of the sixteen
+    sequences."""
+    shape = synth.ModelShape(2, 3584, 28, 4, 128, 18944, 152064)
+    cfg = synth.EpisodeConfig("7b-width", 2, 8, 1100, 2, 124, 4, 64, (1,), 0.3, 0.5)
+    w = synth.make_weights(shape, seed=0)
+    info = {}
+    kw = dict(weights=w, page_tokens=64, kv_pool_bytes=1 << 30)
+    rec, stats, worst, mism, near = run_and_compare(shape, cfg, 0, contract_rows=[0, 5, 11, 14], info=info, **kw)
+    tol = tolerance(info["contract_max"])
+    print(f"full width, prompt 1100: worst |dlogit| = {worst:.3e} (mean {info['gpu_mean']:.3e}); contract mode "
+          f"{info['contract_max']:.3e} (mean {info['contract_mean']:.3e}); bound {tol:.3e}; mismatches = {mism}, "
+          f"near ties = {near}, gaps at the mismatches = {info['mismatch_gaps']}; stats = {stats}")
+    assert stats["cow_page_copies"] > 0
+    assert worst <= tol and info["gpu_mean"] <= 2.0 * info["contract_mean"]
+    assert all(g < gap_rule(tol) for g in info["mismatch_gaps"])
+    _, _, worst32, mism32, _ = run_and_compare(shape, cfg, 0, fp32_debug=True, rec=rec, **kw)
+    print(f"full width, prompt 1100, single precision: worst |dlogit| = {worst32:.3e}")
+    assert worst32 <= FP32_TOL and mism32 == 0
+
+
+def test_group_of_16_with_a_long_shared_prompt():
+    """G = 16 with a shared prompt of several splits at head_dim 128 and 7 query heads per kv head: eight work
+    items of two members each share every prompt block."""
+    shape = synth.ModelShape(2, 512, 14, 2, 128, 1024, 2048)
+    cfg = synth.EpisodeConfig("g16-long", 2, 16, 600, 2, 70, 3, 64, (1,), 0.25, 0.5)
+    info = {}
+    rec, stats, worst, mism, near = run_and_compare(shape, cfg, seed=8, page_tokens=64, contract_rows=[0, 9, 17, 31],
+                                                     info=info)
+    tol = tolerance(info["contract_max"])
+    print(f"G=16, prompt 600: worst |dlogit| = {worst:.3e}; contract mode {info['contract_max']:.3e}; mismatches = {mism}")
+    assert worst <= tol and all(g < gap_rule(tol) for g in info["mismatch_gaps"])
+    _, _, worst32, mism32, _ = run_and_compare(shape, cfg, seed=8, page_tokens=64, fp32_debug=True, rec=rec)
+    assert worst32 <= FP32_TOL and mism32 == 0
+
+
+def test_tied_lm_head_uses_the_embedding_matrix():
+    shape = synth.TINY
+    w = synth.make_weights(shape, seed=0)
+    w.lm_head = w.embed                                               # the checker's model, tied
+    cfg = synth.EpisodeConfig("tied", 2, 4, 32, 1, 8, 3, 16, (), 0.3, 0.5)
+    conv = synth.converging_groups(cfg, 1)
+    prompts = synth.prompts(cfg, shape.vocab, 1)
+    obs = synth.observations(cfg, shape.vocab, 1, 0, conv)
+    rec = oracle.run_episode(oracle.Model(w), prompts, lambda t: obs, cfg.G, 1, cfg.act_len, cfg.action_mod, (), 0.3,
+                             keep_logits=True)
+    ctx = sr.Context(shape, cfg.n_groups, cfg.G, 0.3, page_tokens=32, max_seq_len=64, max_turns=1, action_mod=16,
+                     kv_pool_bytes=1 << 26, tied_lm_head=True)
+    from paper_2605_05802_amd.runner import upload_bits
+    layers = [{k: upload_bits(v) for k, v in d.items()} for d in w.layers]
+    ctx.sr_load_weights(upload_bits(w.embed), None, upload_bits(w.final_norm), layers)   # no separate LM head
+    ctx.sr_prefill_chunk(dev(prompts), True)
+    ctx.sr_prefill_chunk(dev(obs), False)
+    logits = torch.empty((8, shape.vocab), dtype=torch.float32, device="cuda")
+    ctx.sr_get_logits(logits)
+    torch.cuda.synchronize()
+    ref = np.stack([rec["logits"][0][0][r] for r in range(8)])
+    assert np.abs(logits.cpu().numpy() - ref).max() <= LOGIT_TOL
+    ctx.close()
+    # an untied context without an LM head is refused
+    ctx = sr.Context(shape, 2, 4, 0.3, page_tokens=32, max_seq_len=64, max_turns=1, action_mod=16, kv_pool_bytes=1 << 26)
+    with pytest.raises(sr.SrError) as e:
+        ctx.sr_load_weights(upload_bits(w.embed), None, upload_bits(w.final_norm), layers)
+    assert e.value.status == sr.SR_E_ARG
+    ctx.close()
+
+
+def test_finishing_members_between_gate_and_compaction_is_refused():
+    """The pending retire mask is indexed by the groups that were live at the gate; removing a whole group before
+    it is applied would shift it onto other groups, so the call is refused and the order gate -> compact -> finish
+    (or finish -> gate -> compact) is the only legal one."""
+    shape = synth.ModelShape(1, 128, 4, 2, 64, 256, 256)
+    w = synth.make_weights(shape, seed=0)
+    ctx = sr.Context(shape, 3, 2, 0.3, page_tokens=32, max_seq_len=128, max_turns=4, action_mod=16, kv_pool_bytes=1 << 24)
+    load_host_weights(ctx, w)
+    ctx.sr_prefill_chunk(dev(synth.uniform_ids(96, 0, 1, 256).reshape(3, 32)), True)
+    ctx.sr_prefill_chunk(dev(synth.uniform_ids(6 * 8, 0, 2, 256).reshape(6, 8)), False)
+    ctx.sr_decode_step()
+    ctx.sr_gate(1)
+    done = np.array([1, 1, 0, 0, 0, 0], dtype=np.uint8)               # would remove group 0 entirely
+    with pytest.raises(sr.SrError) as e:
+        ctx.sr_finish_sequences(done)
+    assert e.value.status == sr.SR_E_STATE
+    assert ctx.sr_stats()["n_live_seq"] == 6                          # nothing was changed
+    n_live = ctx.sr_retire_and_compact()
+    left = ctx.sr_stats()["n_live_seq"]
+    assert left == 2 * n_live
+    if left:
+        d2 = np.zeros(left, dtype=np.uint8)
+        d2[0] = 1
+        assert ctx.sr_finish_sequences(d2) == left - 1                # legal again after the compaction
+    ctx.close()
+
+
+def _episode_properties(cfg, turns, gate_turns):
+    """Runs `turns` turns of cfg at the 7B shape on the GPU alone, gating after each turn in `gate_turns`, and
+    checks what must hold at any size: converging groups (identical prompts and observations) stay bit-identical
+    row by row, have pair-distance sum 0 and are retired at the first gate; every decision is Eq. 2 applied to
+    the reported sum; survivors keep their order; token and page accounting follow the closed forms."""
     shape = synth.QWEN7B
     seed = 0
+    gate_turns = (gate_turns,) if isinstance(gate_turns, int) else tuple(gate_turns)
     conv = synth.converging_groups(cfg, seed)
     prompts = synth.prompts(cfg, shape.vocab, seed)
     G, n_seq = cfg.G, cfg.n_groups * cfg.G
@@ -521,44 +726,56 @@ def _episode_properties(cfg, turns, gate_turn):
     torch.cuda.empty_cache()
     ctx.sr_prefill_chunk(dev(prompts), True)
     rows = np.arange(n_seq)
-    n_cut = None
+    live_groups = list(range(cfg.n_groups))
+    decoded = 0
     for turn in range(turns):
         ctx.sr_prefill_chunk(dev(synth.observations(cfg, shape.vocab, seed, turn, conv)[rows]), False)
         for _ in range(cfg.act_len):
             ctx.sr_decode_step()
-        if turn + 1 == gate_turn:
+        decoded += len(rows) * cfg.act_len
+        K = turn + 1
+        if K in gate_turns:
+            ng = len(live_groups)
             logits = torch.empty((len(rows), shape.vocab), dtype=torch.float32, device="cuda")
             ctx.sr_get_logits(logits)
             acts = torch.empty((len(rows), turns), dtype=torch.int32, device="cuda")
             ctx.sr_get_actions(acts)
-            sums = torch.empty(cfg.n_groups, dtype=torch.int32, device="cuda")
-            ret = torch.empty(cfg.n_groups, dtype=torch.uint8, device="cuda")
+            sums = torch.empty(ng, dtype=torch.int32, device="cuda")
+            ret = torch.empty(ng, dtype=torch.uint8, device="cuda")
             before = ctx.sr_stats()
-            ctx.sr_gate(gate_turn, sums, ret)
+            ctx.sr_gate(K, sums, ret)
             n_live = ctx.sr_retire_and_compact()
             torch.cuda.synchronize()
             lg, ac, s, r = logits.cpu().numpy(), acts.cpu().numpy(), sums.cpu().numpy(), ret.cpu().numpy()
             assert np.all(np.isfinite(lg))
-            for g in range(cfg.n_groups):
+            for i, g in enumerate(live_groups):
                 if conv[g]:
-                    assert np.all(lg[g * G:(g + 1) * G] == lg[g * G])          # bit-identical rows
-                    assert np.all(ac[g * G:(g + 1) * G, :gate_turn] == ac[g * G, :gate_turn])
-                    assert s[g] == 0 and r[g] == 1
-            assert np.all((ac[:, :gate_turn] >= 0) & (ac[:, :gate_turn] < cfg.action_mod))
-            bound = oracle.gate_bound(cfg.threshold, G, gate_turn)
+                    assert K == gate_turns[0]                                  # none survives its first gate
+                    assert np.all(lg[i * G:(i + 1) * G] == lg[i * G])          # bit-identical rows
+                    assert np.all(ac[i * G:(i + 1) * G, :K] == ac[i * G, :K])
+                    assert s[i] == 0 and r[i] == 1
+            assert np.all((ac[:, :K] >= 0) & (ac[:, :K] < cfg.action_mod))
+            bound = oracle.gate_bound(cfg.threshold, G, K)
             assert np.array_equal(r.astype(bool), s < bound)                    # Eq. 2 on the sums it reports
+            # the reported sums are the pair-distance sums of the reported actions (sampled groups, on the CPU)
+            for i in list(range(0, ng, max(1, ng // 6)))[:6]:
+                assert s[i] == oracle.pair_sum(ac[i * G:(i + 1) * G], K)
             n_cut = int(r.sum())
-            assert n_live == cfg.n_groups - n_cut and n_cut >= conv.sum()
+            assert n_live == ng - n_cut
+            live_groups = [g for i, g in enumerate(live_groups) if not r[i]]
             rows = ctx.sr_get_live_map()
-            assert list(rows) == [g * G + m for g in range(cfg.n_groups) if not r[g] for m in range(G)]
+            assert list(rows) == [g * G + m for g in live_groups for m in range(G)]
             after = ctx.sr_stats()
-            ctx_len = cfg.prompt_len + gate_turn * (cfg.obs_len + cfg.act_len)
+            ctx_len = cfg.prompt_len + K * (cfg.obs_len + cfg.act_len)
             shared_pages = cfg.prompt_len // 64
             priv_pages = -(-ctx_len // 64) - shared_pages
             assert before["pages_in_use"] - after["pages_in_use"] == n_cut * (shared_pages + G * priv_pages)
     stats = ctx.sr_stats()
-    f = (n_cut or 0) / cfg.n_groups
-    assert stats["decoded_tokens"] == round(n_seq * cfg.act_len * (turns - f * (turns - gate_turn)))
+    assert stats["decoded_tokens"] == decoded
+    if len(gate_turns) == 1:      # Table 1's closed form for a single gate: n_seq * A * (T - f * (T - K))
+        f = stats["groups_retired"] / cfg.n_groups
+        assert decoded == round(n_seq * cfg.act_len * (turns - f * (turns - gate_turns[0])))
+    assert stats["groups_retired"] == cfg.n_groups - len(live_groups) >= conv.sum()
     assert stats["seq_len"] == max_len
     ctx.close()
     return stats
@@ -577,3 +794,12 @@ def test_512_sequence_batch_at_the_7b_shape():
     prompt 1024, three turns with the gate after the second."""
     stats = _episode_properties(synth.C4_EPISODE, 3, 2)
     print(f"512-row episode: {stats}")
+
+
+def test_group_size_16_batch_with_a_4096_token_prompt_at_the_7b_shape():
+    """32 groups x G=16 = 512 rows, shared prompt of 4096 tokens (16 shared splits, eight work items of two members
+    per prompt block), 128-token observation chunks (65 536 rows per prefill: eight passes), threshold 0.25, two
+    gate turns -- here after turns 2 and 4 of 5, so that both gates and the second compaction run in seconds."""
+    stats = _episode_properties(synth.C5_EPISODE, 5, (2, 4))
+    print(f"G=16 episode: {stats}")
+    assert stats["groups_retired"] >= 13

@@ -183,23 +183,6 @@ def test_episode_with_members_that_finish_early():
     assert rec2["gate"][3]["cut"] == {0: True, 1: True, 3: False} and rec2["final_live_groups"] == [3]
 
 
-def test_bf16_contract_mode_is_off_by_default_and_small(small):
-    """The contract mode only rounds activations to bf16: it must stay close to the exact evaluation
-    (relative 2^-9 roundings) and must not leak into later exact evaluations."""
-    tokens = synth.uniform_ids(12, 3, 55, SMALL.vocab)
-    m = oracle.Model(small)
-    exact = m.new_seq(32).forward(tokens)
-    oracle.set_bf16_contract(True)
-    try:
-        rounded = m.new_seq(32).forward(tokens)
-    finally:
-        oracle.set_bf16_contract(False)
-    again = m.new_seq(32).forward(tokens)
-    assert np.array_equal(exact, again)
-    d = np.abs(rounded - exact).max()
-    assert 0 < d < 0.05 * np.abs(exact).max()
-
-
 def test_sampler_draws_from_softmax():
     """Gumbel-max sampling with counter-based uniforms: empirical frequencies over many (sequence,
     position) keys match softmax(logits / T); draws are reproducible and keyed, not positional."""
