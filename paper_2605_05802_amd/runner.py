@@ -1,7 +1,4 @@
-"""Episode driver on top of the C boundary: uploads weights and walks the turn loop.
-
-Marshalling and control flow only (which call comes next); every number is produced by libsr.so.
-"""
+"""Weight upload helpers on top of the C boundary (marshalling only; every number is produced by libsr.so)."""
 from __future__ import annotations
 
 import numpy as np
@@ -22,27 +19,3 @@ def load_host_weights(ctx: Context, w, n_layers=None):
     layers = [{k: upload_bits(v) for k, v in w.layers[l].items()} for l in range(L)]
     ctx.sr_load_weights(embed, lm, fn, layers)
     torch.cuda.synchronize()
-
-
-class Episode:
-    """One gated rollout: prompt prefill, then per turn an observation chunk and act_len decode steps."""
-
-    def __init__(self, ctx: Context, G: int, act_len: int, gate_turns=()):
-        self.ctx, self.G, self.act_len, self.gate_turns = ctx, G, act_len, tuple(gate_turns)
-        self.turn = 0
-
-    def prefill_prompt(self, prompts_dev):
-        self.ctx.sr_prefill_chunk(prompts_dev, True)
-
-    def run_turn(self, obs_dev, forced=None, out_tokens=None):
-        """obs_dev: int32 [n_live_seq, obs_len] on the device.  forced/out_tokens: optional lists of
-        act_len device tensors.  Returns the number of live groups after the (possible) gate."""
-        self.ctx.sr_prefill_chunk(obs_dev, False)
-        for a in range(self.act_len):
-            self.ctx.sr_decode_step(None if forced is None else forced[a],
-                                    None if out_tokens is None else out_tokens[a])
-        self.turn += 1
-        if self.turn in self.gate_turns:
-            self.ctx.sr_gate(self.turn)
-            return self.ctx.sr_retire_and_compact()
-        return None
