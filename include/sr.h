@@ -44,7 +44,8 @@ typedef enum {
     SR_E_ARG = -1,    /* null pointer, bad shape, turn out of range, chunk_len <= 0, G < 2, ... */
     SR_E_NOMEM = -2,  /* KV page pool exhausted (checked on the host before any launch) or allocation failed */
     SR_E_STATE = -3,  /* call out of order: decode before prefill, gate with too few recorded actions, ... */
-    SR_E_HIP = -4     /* a HIP runtime call failed; sr_strerror gives the text */
+    SR_E_HIP = -4,    /* a HIP runtime call failed; sr_strerror gives the text */
+    SR_E_LIMIT = -5   /* a size beyond the fixed capacity of an entry point that allocates nothing */
 } sr_status;
 
 typedef struct sr_ctx sr_ctx;
@@ -254,6 +255,19 @@ int sr_get_logprob(sr_ctx *ctx, double *dst, void *stream);
  */
 int sr_grpo_loss(const double *logprob, const float *rewards, int n_groups, int G, double eps,
                  float *advantages, double *group_scratch, double *loss, void *stream);
+
+/*
+ * sr_grpo_loss for callers that cannot allocate device memory or bring a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without group_scratch,
+ * same kernel, same results bit for bit; the per-group shares go to a fixed device array inside the library
+ * (SR_GRPO_STATIC_MAX_GROUPS doubles = 512 KiB, held by every GPU the library runs on until the process
+ * ends).  The call allocates and frees nothing.  n_groups above the limit: SR_E_LIMIT, nothing is launched.
+ * All calls on one GPU share that array: calls that may overlap on one GPU (different streams) race and
+ * must be serialised by the caller; nothing of an earlier call's contents is read.
+ */
+#define SR_GRPO_STATIC_MAX_GROUPS 65536
+int sr_grpo_loss_static(const double *logprob, const float *rewards, int n_groups, int G, double eps,
+                        float *advantages, double *loss, void *stream);
 
 /*
  * The in-group divergence signals of Appendix B at step K, and the gates of Eq. 2 and of

@@ -13,12 +13,13 @@ from .build import LIB, build
 
 _lib = None
 
-SR_OK, SR_E_ARG, SR_E_NOMEM, SR_E_STATE, SR_E_HIP = 0, -1, -2, -3, -4
+SR_OK, SR_E_ARG, SR_E_NOMEM, SR_E_STATE, SR_E_HIP, SR_E_LIMIT = 0, -1, -2, -3, -4, -5
+GRPO_STATIC_MAX_GROUPS = 65536
 
 EXPORTS = ("sr_init", "sr_destroy", "sr_load_weights", "sr_prefill_chunk", "sr_decode_step", "sr_gate",
            "sr_retire_and_compact", "sr_gate_batch", "sr_set_actions", "sr_get_actions", "sr_get_logits",
            "sr_get_live_map", "sr_stats", "sr_strerror", "sr_profile", "sr_profile_read", "sr_signals_batch",
-           "sr_score_chunk", "sr_get_logprob", "sr_grpo_loss", "sr_finish_sequences")
+           "sr_score_chunk", "sr_get_logprob", "sr_grpo_loss", "sr_finish_sequences", "sr_grpo_loss_static")
 
 KERNEL_CLASSES = ("norm", "gemm_qkv", "qkv_post", "attn_decode", "attn_prefill", "attn_merge",
                   "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm_head", "argmax")
@@ -91,6 +92,7 @@ def lib():
         L.sr_score_chunk.argtypes = [vp, vp, vp, ci, vp, vp]
         L.sr_get_logprob.argtypes = [vp, vp, vp]
         L.sr_grpo_loss.argtypes = [vp, vp, ci, ci, ctypes.c_double, vp, vp, vp, vp]
+        L.sr_grpo_loss_static.argtypes = [vp, vp, ci, ci, ctypes.c_double, vp, vp, vp]
         L.sr_finish_sequences.argtypes = [vp, vp, ctypes.POINTER(ci), vp]
         L.sr_set_actions.argtypes = [vp, ci, vp, vp]
         L.sr_get_actions.argtypes = [vp, vp, vp]
@@ -162,6 +164,13 @@ def sr_grpo_loss(logprob, rewards, G: int, eps: float, advantages, group_scratch
     n_groups = logprob.numel() // G
     _check(lib().sr_grpo_loss(_ptr(logprob), _ptr(rewards), n_groups, G, eps, _ptr(advantages), _ptr(group_scratch),
                               _ptr(loss), _stream(stream)), "sr_grpo_loss")
+
+
+def sr_grpo_loss_static(logprob, rewards, G: int, eps: float, advantages, loss, stream=None):
+    """sr_grpo_loss without a workspace argument (the library's fixed device array holds the group shares)."""
+    n_groups = logprob.numel() // G
+    _check(lib().sr_grpo_loss_static(_ptr(logprob), _ptr(rewards), n_groups, G, eps, _ptr(advantages), _ptr(loss),
+                                     _stream(stream)), "sr_grpo_loss_static")
 
 
 class Context:

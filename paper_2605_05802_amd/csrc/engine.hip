@@ -691,6 +691,7 @@ const char *sr_strerror(int status) {
         case SR_E_NOMEM: return "out of memory (KV page pool exhausted or allocation failed)";
         case SR_E_STATE: return "call out of order";
         case SR_E_HIP: return g_hip_error.empty() ? "HIP error" : g_hip_error.c_str();
+        case SR_E_LIMIT: return "size beyond the fixed capacity of an entry point that allocates nothing";
         default: return "unknown status";
     }
 }

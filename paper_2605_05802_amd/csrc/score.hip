@@ -11,6 +11,8 @@
 // grpo_loss_kernel: one thread per group computes the advantages of Eq. 1 (population standard
 // deviation; exactly zero when all rewards of the group are equal) and the group's share of
 // sum_i A_i log p(tau_i); thread 0 adds the shares in group order.
+#include <mutex>
+
 #include "sr_internal.h"
 
 namespace sr {
@@ -123,6 +125,51 @@ extern "C" int sr_grpo_loss(const double *logprob, const float *rewards, int n_g
     if (!logprob || !rewards || !group_scratch || !loss || n_groups < 1 || G < 1 || !(eps >= 0.0)) return SR_E_ARG;
     sr::grpo_loss_kernel<<<dim3(1), dim3(256), 0, (hipStream_t)stream>>>(logprob, rewards, n_groups, G, eps, advantages,
                                                                          group_scratch, loss);
+    SR_HIP(hipGetLastError());
+    return SR_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// The same loss for callers that cannot allocate: the per-group shares live in a file-scope device
+// array instead of a buffer the caller brings.
+// ---------------------------------------------------------------------------------------------
+namespace {
+
+constexpr int kStaticMaxGroups = SR_GRPO_STATIC_MAX_GROUPS;
+static __device__ __align__(256) double scratch[kStaticMaxGroups];   // every GPU holds its own copy
+
+constexpr int kMaxDevices = 64;
+double *g_scratch_ptr[kMaxDevices];        // device address of `scratch` on each GPU, looked up once
+bool g_scratch_known[kMaxDevices];
+std::mutex g_scratch_mutex;
+
+// Device address of this GPU's copy of `scratch` (the array's name is only a host-side stand-in).
+int static_scratch(double **out) {
+    int dev = -1;
+    SR_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return SR_E_ARG;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_known[dev]) {
+        void *p = nullptr;
+        SR_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        g_scratch_ptr[dev] = (double *)p;
+        g_scratch_known[dev] = true;
+    }
+    *out = g_scratch_ptr[dev];
+    return SR_OK;
+}
+
+}  // namespace
+
+extern "C" int sr_grpo_loss_static(const double *logprob, const float *rewards, int n_groups, int G, double eps,
+                                   float *advantages, double *loss, void *stream) {
+    if (!logprob || !rewards || !loss || n_groups < 1 || G < 1 || !(eps >= 0.0)) return SR_E_ARG;
+    if (n_groups > kStaticMaxGroups) return SR_E_LIMIT;
+    double *share = nullptr;
+    SR_TRY(static_scratch(&share));
+    // every share[g], g < n_groups, is written before it is read: nothing of an earlier call is used
+    sr::grpo_loss_kernel<<<dim3(1), dim3(256), 0, (hipStream_t)stream>>>(logprob, rewards, n_groups, G, eps, advantages,
+                                                                         share, loss);
     SR_HIP(hipGetLastError());
     return SR_OK;
 }
