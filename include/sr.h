@@ -364,6 +364,20 @@ typedef struct {
 int sr_profile(sr_ctx *ctx, int enable);
 int sr_profile_read(sr_ctx *ctx, sr_kernel_time *host_out /* [SR_KC_COUNT] */, void *stream);
 
+/*
+ * Measured ceilings of the chip, for the roofline report next to the published peaks (HBM 8 TB/s, dense
+ * bf16 matrix cores 2.5 PFLOP/s).  Both calls launch probe kernels on `stream`, time `iters` launches with
+ * HIP events, wait for them and write the rate to a HOST double.  They are not part of the method.
+ *   sr_probe_hbm: src (device, `bytes` long; use well over 256 MiB so that no cache holds it) is streamed by
+ *     4096 wavefronts with 16-byte loads -- mode 0 with the non-temporal hint of the weight-streaming kernels,
+ *     mode 1 with default loads, mode 2 copied to dst (device, `bytes` long; read + written bytes are counted).
+ *     For modes 0 and 1 dst must point at >= 16 device bytes (never written in practice).
+ *   sr_probe_mfma_bf16: register-resident 32x32x16 bf16 matrix-core loop on 1024 workgroups; scratch is
+ *     device memory of at least 1 MiB that receives one float per thread.
+ */
+int sr_probe_hbm(const void *src, void *dst, size_t bytes, int mode, int iters, void *stream, double *host_GBs);
+int sr_probe_mfma_bf16(void *scratch, size_t scratch_bytes, int iters, void *stream, double *host_TFLOPs);
+
 /* Text for a status code; for SR_E_HIP the text of the last HIP error seen by this thread. */
 const char *sr_strerror(int status);
 

@@ -19,7 +19,8 @@ GRPO_STATIC_MAX_GROUPS = 65536
 EXPORTS = ("sr_init", "sr_destroy", "sr_load_weights", "sr_prefill_chunk", "sr_decode_step", "sr_gate",
            "sr_retire_and_compact", "sr_gate_batch", "sr_set_actions", "sr_get_actions", "sr_get_logits",
            "sr_get_live_map", "sr_stats", "sr_strerror", "sr_profile", "sr_profile_read", "sr_signals_batch",
-           "sr_score_chunk", "sr_get_logprob", "sr_grpo_loss", "sr_finish_sequences", "sr_grpo_loss_static")
+           "sr_score_chunk", "sr_get_logprob", "sr_grpo_loss", "sr_finish_sequences", "sr_grpo_loss_static",
+           "sr_probe_hbm", "sr_probe_mfma_bf16")
 
 KERNEL_CLASSES = ("norm", "gemm_qkv", "qkv_post", "attn_decode", "attn_prefill", "attn_merge",
                   "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm_head", "argmax")
@@ -93,6 +94,8 @@ def lib():
         L.sr_get_logprob.argtypes = [vp, vp, vp]
         L.sr_grpo_loss.argtypes = [vp, vp, ci, ci, ctypes.c_double, vp, vp, vp, vp]
         L.sr_grpo_loss_static.argtypes = [vp, vp, ci, ci, ctypes.c_double, vp, vp, vp]
+        L.sr_probe_hbm.argtypes = [vp, vp, ctypes.c_size_t, ci, ci, vp, ctypes.POINTER(ctypes.c_double)]
+        L.sr_probe_mfma_bf16.argtypes = [vp, ctypes.c_size_t, ci, vp, ctypes.POINTER(ctypes.c_double)]
         L.sr_finish_sequences.argtypes = [vp, vp, ctypes.POINTER(ci), vp]
         L.sr_set_actions.argtypes = [vp, ci, vp, vp]
         L.sr_get_actions.argtypes = [vp, vp, vp]
@@ -171,6 +174,23 @@ def sr_grpo_loss_static(logprob, rewards, G: int, eps: float, advantages, loss, 
     n_groups = logprob.numel() // G
     _check(lib().sr_grpo_loss_static(_ptr(logprob), _ptr(rewards), n_groups, G, eps, _ptr(advantages), _ptr(loss),
                                      _stream(stream)), "sr_grpo_loss_static")
+
+
+def sr_probe_hbm(src, dst, mode: int, iters: int = 10, stream=None) -> float:
+    """GB/s of a streaming read of `src` (mode 0: non-temporal loads, 1: default loads) or of a copy to dst (2)."""
+    out = ctypes.c_double()
+    nbytes = src.numel() * src.element_size()
+    _check(lib().sr_probe_hbm(_ptr(src), _ptr(dst), nbytes, mode, iters, _stream(stream), ctypes.byref(out)),
+           "sr_probe_hbm")
+    return out.value
+
+
+def sr_probe_mfma_bf16(scratch, iters: int = 3, stream=None) -> float:
+    """TFLOP/s of a register-resident bf16 matrix-core loop."""
+    out = ctypes.c_double()
+    _check(lib().sr_probe_mfma_bf16(_ptr(scratch), scratch.numel() * scratch.element_size(), iters, _stream(stream),
+                                    ctypes.byref(out)), "sr_probe_mfma_bf16")
+    return out.value
 
 
 class Context:
