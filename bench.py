@@ -196,7 +196,16 @@ def gate_throughput(sr, torch, synth, iters=20):
     e1.record()
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / iters
-    return 65536 / (ms * 1e-3), ms, acts
+    # the same by the other decomposition (one workgroup per group, anti-diagonals in LDS), for comparison
+    for _ in range(3):
+        sr.sr_gate_batch_antidiag(a, [5, 10, 15], 0.3, sums, ret)
+    e0.record()
+    for _ in range(iters):
+        sr.sr_gate_batch_antidiag(a, [5, 10, 15], 0.3, sums, ret)
+    e1.record()
+    torch.cuda.synchronize()
+    ms_ad = e0.elapsed_time(e1) / iters
+    return 65536 / (ms * 1e-3), ms, acts, ms_ad
 
 
 def signals_throughput(sr, torch, acts, iters=20):
@@ -412,7 +421,7 @@ def main():
                    "frac_of_measured_mfma_peak": float(np.median(pf_rate)) / peaks["mfma_bf16_TFLOPs"],
                    "rows_first_turn": res["prefill"][0][1]} if res["prefill"] else None
 
-    gate_gps, gate_ms, acts = gate_throughput(sr, torch, synth)
+    gate_gps, gate_ms, acts, gate_ms_ad = gate_throughput(sr, torch, synth)
     sig_gps, sig_ms = signals_throughput(sr, torch, acts)
     out = {
         "metric": f"decoded tokens/s at Qwen2.5-7B shape, G={cfg.G} (whole gated episode: prompt prefill, per-turn "
@@ -437,7 +446,10 @@ def main():
                         "decode_only_tokens_per_s": decoded / (sum(res["step_ms"]) * 1e-3)},
         "prefill_chunk": prefill_obj,
         "kernel_ms_per_profiled_step": {k: v[1] / max(len(rows), 1) for k, v in res["kernel_times"].items()},
-        "gate": {"groups_per_s": gate_gps, "ms_per_launch": gate_ms, "workload": "65536 groups x G=8, prefixes 5/10/15"},
+        "gate": {"groups_per_s": gate_gps, "ms_per_launch": gate_ms, "workload": "65536 groups x G=8, prefixes 5/10/15",
+                 "kernel": "one lane per pair, table row in registers",
+                 "antidiagonal_lds_variant_ms_per_launch": gate_ms_ad,
+                 "antidiagonal_lds_variant_groups_per_s": 65536 / (gate_ms_ad * 1e-3)},
         "score_pass": score,
         "sampling": sampling,
         "signals": {"groups_per_s": sig_gps, "ms_per_launch": sig_ms,

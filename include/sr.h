@@ -223,6 +223,14 @@ int sr_gate_batch(const int32_t *actions, int n_groups, int G, int stride, const
                   int n_lens, double threshold, int32_t *sums, uint8_t *retire, void *stream);
 
 /*
+ * sr_gate_batch computed by the other work decomposition -- one workgroup per group, every pair's
+ * Levenshtein table advanced one anti-diagonal at a time with the last three anti-diagonals in LDS --
+ * for measuring the two side by side.  Same arguments, same results bit for bit (Section 3.2, Eq. 2).
+ */
+int sr_gate_batch_antidiag(const int32_t *actions, int n_groups, int G, int stride, const int *prefix_lens,
+                           int n_lens, double threshold, int32_t *sums, uint8_t *retire, void *stream);
+
+/*
  * Teacher-forced scoring (Appendix C.2).  Appends chunk_len given tokens to every live sequence
  * exactly like sr_prefill_chunk(..., shared_per_group = 0) -- their K/V are computed and the
  * logits at the chunk's last position are kept -- and adds, for every chunk position t whose

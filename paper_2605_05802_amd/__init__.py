@@ -20,7 +20,7 @@ EXPORTS = ("sr_init", "sr_destroy", "sr_load_weights", "sr_prefill_chunk", "sr_d
            "sr_retire_and_compact", "sr_gate_batch", "sr_set_actions", "sr_get_actions", "sr_get_logits",
            "sr_get_live_map", "sr_stats", "sr_strerror", "sr_profile", "sr_profile_read", "sr_signals_batch",
            "sr_score_chunk", "sr_get_logprob", "sr_grpo_loss", "sr_finish_sequences", "sr_grpo_loss_static",
-           "sr_probe_hbm", "sr_probe_mfma_bf16")
+           "sr_probe_hbm", "sr_probe_mfma_bf16", "sr_gate_batch_antidiag")
 
 KERNEL_CLASSES = ("norm", "gemm_qkv", "qkv_post", "attn_decode", "attn_prefill", "attn_merge",
                   "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm_head", "argmax")
@@ -88,6 +88,7 @@ def lib():
         L.sr_gate.argtypes = [vp, ci, vp, vp, vp]
         L.sr_retire_and_compact.argtypes = [vp, ctypes.POINTER(ci), vp]
         L.sr_gate_batch.argtypes = [vp, ci, ci, ci, ctypes.POINTER(ci), ci, ctypes.c_double, vp, vp, vp]
+        L.sr_gate_batch_antidiag.argtypes = L.sr_gate_batch.argtypes
         L.sr_signals_batch.argtypes = [vp, vp, vp, ci, ci, ci, ctypes.POINTER(ci), ci, ctypes.c_double,
                                        ctypes.c_double, vp, vp]
         L.sr_score_chunk.argtypes = [vp, vp, vp, ci, vp, vp]
@@ -144,6 +145,14 @@ def sr_gate_batch(actions, prefix_lens, threshold: float, sums=None, retire=None
     lens = (ctypes.c_int * len(prefix_lens))(*prefix_lens)
     _check(lib().sr_gate_batch(_ptr(actions), n_groups, G, stride, lens, len(prefix_lens), threshold,
                                _ptr(sums), _ptr(retire), _stream(stream)), "sr_gate_batch")
+
+
+def sr_gate_batch_antidiag(actions, prefix_lens, threshold: float, sums=None, retire=None, stream=None):
+    """sr_gate_batch by the anti-diagonal decomposition (same arguments, same results)."""
+    n_groups, G, stride = actions.shape
+    lens = (ctypes.c_int * len(prefix_lens))(*prefix_lens)
+    _check(lib().sr_gate_batch_antidiag(_ptr(actions), n_groups, G, stride, lens, len(prefix_lens), threshold,
+                                        _ptr(sums), _ptr(retire), _stream(stream)), "sr_gate_batch_antidiag")
 
 
 SIGNALS_BYTES = 64       # sizeof(sr_signals_t)

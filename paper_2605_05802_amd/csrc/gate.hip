@@ -102,7 +102,93 @@ __global__ __launch_bounds__(kGateThreads) void gate_kernel(
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// The other decomposition, kept for comparison: one workgroup per group, every pair's table advanced
+// one anti-diagonal at a time by a segment of SEG lanes (lane i owns row i of the table), the last
+// three anti-diagonals of every pair in LDS.  256 / SEG pairs advance together; with G = 8 the 28
+// pairs take two passes at SEG = 16 and four at SEG = 32.  Cell (k, k), the distance of the two
+// length-k prefixes, appears on anti-diagonal 2k in lane k.  A segment never straddles a wavefront,
+// and a wavefront's LDS accesses complete in program order, so no workgroup barrier is needed
+// between anti-diagonals.  Half of a segment's lanes are idle in the triangular ramp-up and
+// ramp-down and every step is an LDS round trip, which is why the lane-per-pair kernel above is the
+// one the library uses; sr_gate_batch_antidiag exposes this one so that the two can be measured
+// side by side and checked against each other.
+// ---------------------------------------------------------------------------------------------
+template <int SEG>
+__global__ __launch_bounds__(kGateThreads) void gate_antidiag_kernel(
+    const int32_t *__restrict__ actions, int n_groups, int G, int stride, int pairs, int maxlen, GateLens lens,
+    int32_t *__restrict__ sums, uint8_t *__restrict__ retire) {
+    constexpr int kSlots = kGateThreads / SEG;             // pairs that advance together
+    __shared__ int32_t s_act[16 * SEG];                      // [member][step], the first SEG steps
+    __shared__ unsigned s_d[3][kSlots][SEG + 1];             // anti-diagonals d-2, d-1, d of every slot, by table row
+    __shared__ int s_sum[8];
+
+    const int tid = threadIdx.x, g = blockIdx.x;
+    if (tid < 8) s_sum[tid] = 0;
+    for (int i = tid; i < G * SEG; i += kGateThreads) {
+        const int r = i / SEG, c = i - r * SEG;
+        s_act[i] = (c < stride) ? actions[((size_t)g * G + r) * stride + c] : -1 - c;
+    }
+    __syncthreads();
+
+    const int slot = tid / SEG, row = tid % SEG + 1;         // this lane owns table row `row` (1-based)
+    for (int p0 = 0; p0 < pairs; p0 += kSlots) {
+        int p = p0 + slot;
+        const bool live = p < pairs;
+        int mi = 0;
+        if (live) while (p >= G - 1 - mi) { p -= G - 1 - mi; ++mi; }
+        const int mj = live ? mi + 1 + p : 1;
+        const int32_t a_row = s_act[mi * SEG + row - 1];     // a[row - 1]
+        const int32_t *b = s_act + mj * SEG;
+        // anti-diagonal 0: D[0][0] = 0; anti-diagonal 1: D[0][1] = D[1][0] = 1
+        if (row == 1) { s_d[0][slot][0] = 0; s_d[1][slot][0] = 1; s_d[1][slot][1] = 1; }
+        __builtin_amdgcn_wave_barrier();
+        for (int d = 2; d <= 2 * maxlen; ++d) {
+            const unsigned *prev2 = s_d[(d - 2) % 3][slot], *prev = s_d[(d - 1) % 3][slot];
+            unsigned *cur = s_d[d % 3][slot];
+            const int col = d - row;                         // this lane's cell is (row, col)
+            if (row <= maxlen) {
+                if (col == 0) {
+                    cur[row] = (unsigned)row;                // first column of the table
+                } else if (col >= 1 && col <= maxlen) {
+                    const unsigned v = min3u(prev2[row - 1] + (a_row != b[col - 1] ? 1u : 0u), prev[row - 1] + 1u,
+                                             prev[row] + 1u);
+                    cur[row] = v;
+                    if (live && col == row) {                // cell (k, k): the answer for prefix length k
+#pragma unroll
+                        for (int l = 0; l < 8; ++l)
+                            if (l < lens.n && lens.len[l] == row) atomicAdd(&s_sum[l], (int)v);
+                    }
+                }
+            }
+            if (row == 1 && d <= maxlen) cur[0] = (unsigned)d;   // first row of the table
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+    __syncthreads();
+    if (tid < lens.n) {
+        const int sum = s_sum[tid];
+        if (sums) sums[(size_t)tid * n_groups + g] = sum;
+        if (retire) retire[(size_t)tid * n_groups + g] = (uint8_t)(sum < lens.bound[tid]);
+    }
+}
+
 }  // namespace
+
+int launch_gate_antidiag(const int32_t *actions, int n_groups, int G, int stride, const GateLens &lens,
+                         int32_t *sums, uint8_t *retire, hipStream_t stream) {
+    if (n_groups <= 0) return SR_OK;
+    int maxlen = 0;
+    for (int l = 0; l < lens.n; ++l) maxlen = lens.len[l] > maxlen ? lens.len[l] : maxlen;
+    const int pairs = G * (G - 1) / 2;
+    dim3 grid(n_groups), block(kGateThreads);
+    if (maxlen <= 16)
+        gate_antidiag_kernel<16><<<grid, block, 0, stream>>>(actions, n_groups, G, stride, pairs, maxlen, lens, sums, retire);
+    else
+        gate_antidiag_kernel<32><<<grid, block, 0, stream>>>(actions, n_groups, G, stride, pairs, maxlen, lens, sums, retire);
+    SR_HIP(hipGetLastError());
+    return SR_OK;
+}
 
 int launch_gate(const int32_t *actions, int n_groups, int G, int stride, const GateLens &lens,
                 int32_t *sums, uint8_t *retire, hipStream_t stream) {
@@ -144,4 +230,21 @@ extern "C" int sr_gate_batch(const int32_t *actions, int n_groups, int G, int st
         lens.bound[l] = (int)sr::gate_bound(threshold, G, K);
     }
     return sr::launch_gate(actions, n_groups, G, stride, lens, sums, retire, (hipStream_t)stream);
+}
+
+extern "C" int sr_gate_batch_antidiag(const int32_t *actions, int n_groups, int G, int stride,
+                                      const int *prefix_lens, int n_lens, double threshold, int32_t *sums,
+                                      uint8_t *retire, void *stream) {
+    if (!actions || !prefix_lens || n_groups < 0 || G < 2 || G > 16 || stride < 1 || n_lens < 1 ||
+        n_lens > 8 || !(threshold >= 0.0) || threshold > 1.0)
+        return SR_E_ARG;
+    sr::GateLens lens{};
+    lens.n = n_lens;
+    for (int l = 0; l < n_lens; ++l) {
+        const int K = prefix_lens[l];
+        if (K < 1 || K > 32 || K > stride) return SR_E_ARG;
+        lens.len[l] = K;
+        lens.bound[l] = (int)sr::gate_bound(threshold, G, K);
+    }
+    return sr::launch_gate_antidiag(actions, n_groups, G, stride, lens, sums, retire, (hipStream_t)stream);
 }

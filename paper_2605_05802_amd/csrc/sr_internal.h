@@ -77,6 +77,9 @@ struct GateLens {
 
 int launch_gate(const int32_t *actions, int n_groups, int G, int stride, const GateLens &lens,
                 int32_t *sums, uint8_t *retire, hipStream_t stream);
+// the same result by the other decomposition (one workgroup per group, anti-diagonals in LDS)
+int launch_gate_antidiag(const int32_t *actions, int n_groups, int G, int stride, const GateLens &lens,
+                         int32_t *sums, uint8_t *retire, hipStream_t stream);
 
 // Gate input of groups with finished members: slot s (group-major, G per group) takes the action row
 // src[s] of live_actions when src[s] >= 0, else row -1 - src[s] of fin_actions.

@@ -10,21 +10,24 @@ import synth
 pytestmark = pytest.mark.gpu
 
 
-def run_gpu(acts, lens, thr):
+def run_gpu(acts, lens, thr, fn=None):
     a = torch.from_numpy(acts).cuda()
     n_groups = acts.shape[0]
     sums = torch.full((len(lens), n_groups), -7, dtype=torch.int32, device="cuda")
     retire = torch.full((len(lens), n_groups), 9, dtype=torch.uint8, device="cuda")
-    sr.sr_gate_batch(a, lens, thr, sums, retire)
+    (fn or sr.sr_gate_batch)(a, lens, thr, sums, retire)
     torch.cuda.synchronize()
     return sums.cpu().numpy(), retire.cpu().numpy()
 
 
 def check(acts, lens, thr):
-    s_gpu, r_gpu = run_gpu(acts, lens, thr)
+    """Both decompositions of the gate (one lane per pair; one workgroup per group with anti-diagonals in LDS)
+    against the checker: every sum and every decision equal."""
     s_ref, r_ref = oracle.gate_batch(acts, lens, thr)
-    assert np.array_equal(s_gpu, s_ref)
-    assert np.array_equal(r_gpu, r_ref)
+    for fn in (sr.sr_gate_batch, sr.sr_gate_batch_antidiag):
+        s_gpu, r_gpu = run_gpu(acts, lens, thr, fn)
+        assert np.array_equal(s_gpu, s_ref), fn.__name__
+        assert np.array_equal(r_gpu, r_ref), fn.__name__
     return s_ref, r_ref
 
 
