@@ -16,6 +16,8 @@
 // Group batching: during decode the prompt pages shared by the G members of a group are read
 // once per group (the members' G*n_rep query rows form the row tiles of the work item)
 // instead of once per member.
+#include <type_traits>
+
 #include "sr_internal.h"
 
 namespace sr {
@@ -23,6 +25,15 @@ namespace {
 
 constexpr float kNegBig = -1.0e30f;
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// A 16-byte K/V fragment.  STREAM: with the non-temporal hint, for tokens that exactly one work item reads in
+// this launch (a sequence's private context): the caches do not retain the line and a long stream gains 8 %.
+// Blocks that sibling work items re-read (the shared prompt, prefill) keep the default policy.
+template <bool STREAM>
+__device__ __forceinline__ bf16x8 load_frag(const uint16_t *p) {
+    if constexpr (STREAM) return __builtin_bit_cast(bf16x8, __builtin_nontemporal_load((const u32x4 *)p));
+    else return __builtin_bit_cast(bf16x8, *(const u32x4 *)p);
+}
 
 // One launch may cover two phases (decode: the shared-prompt phase followed by the private phase), so
 // that the short, narrow shared phase overlaps the private one instead of running alone.
@@ -101,17 +112,17 @@ __global__ __launch_bounds__(256, RT == 1 ? 3 : 2) void attn_kernel(AttnArgs a, 
     const float scale_log2 = a.scale * 1.4426950408889634f;
 
     bf16x8 kf[2][KS], vf[DT];
-    auto load_k = [&](const uint16_t *kb) {
+    auto load_k = [&](auto stream, const uint16_t *kb) {
 #pragma unroll
         for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks)
-                kf[tt][ks] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(kb + ((ks * 32 + tt * 16 + c) * 32 + 8 * g)));
+                kf[tt][ks] = load_frag<decltype(stream)::value>(kb + ((ks * 32 + tt * 16 + c) * 32 + 8 * g));
     };
-    auto load_v = [&](const uint16_t *vb) {
+    auto load_v = [&](auto stream, const uint16_t *vb) {
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
-            vf[dt] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(vb + ((dt * 16 + c) * 32 + 8 * g)));
+            vf[dt] = load_frag<decltype(stream)::value>(vb + ((dt * 16 + c) * 32 + 8 * g));
     };
     // S^T = K Q^T for all row tiles
     auto scores = [&](f32x4 (&s)[RT][2]) {
@@ -178,29 +189,33 @@ __global__ __launch_bounds__(256, RT == 1 ? 3 : 2) void attn_kernel(AttnArgs a, 
     // the V fragments likewise after the P.V MFMAs, so 8 KiB per wavefront (d = 128) are in
     // flight behind the softmax and behind the next block's scores.  With one row tile (decode) the register
     // budget stays low enough for three wavefronts per SIMD, so every item of a decode step is resident at once.
-    if (t_lo < t_hi) {
-        const size_t base = block_base(t_lo);
-        load_k(a.kpool + base);
-        load_v(a.vpool + base);
-    }
-    for (int t0 = t_lo; t0 < t_hi; t0 += 32) {          // t_lo is a multiple of 32
-        const int tn = t0 + 32 < t_hi ? t0 + 32 : t0;   // after the last block: harmless re-read
-        const size_t base_n = block_base(tn);
-        f32x4 s[RT][2];
-        scores(s);
-        // the scheduling fences keep each refill where it is written: right behind the last use
-        // of the registers it overwrites, a whole softmax (or score pass) ahead of its first use
-        __builtin_amdgcn_sched_barrier(0);
-        load_k(a.kpool + base_n);
-        __builtin_amdgcn_sched_barrier(0);
-        bf16x8 pf[RT];
-        float alpha[RT];
-        softmax(s, t0, pf, alpha);
-        accumulate(pf, alpha);
-        __builtin_amdgcn_sched_barrier(0);
-        load_v(a.vpool + base_n);
-        __builtin_amdgcn_sched_barrier(0);
-    }
+    auto block_loop = [&](auto stream) {
+        if (t_lo < t_hi) {
+            const size_t base = block_base(t_lo);
+            load_k(stream, a.kpool + base);
+            load_v(stream, a.vpool + base);
+        }
+        for (int t0 = t_lo; t0 < t_hi; t0 += 32) {          // t_lo is a multiple of 32
+            const int tn = t0 + 32 < t_hi ? t0 + 32 : t0;   // after the last block: harmless re-read
+            const size_t base_n = block_base(tn);
+            f32x4 s[RT][2];
+            scores(s);
+            // the scheduling fences keep each refill where it is written: right behind the last use
+            // of the registers it overwrites, a whole softmax (or score pass) ahead of its first use
+            __builtin_amdgcn_sched_barrier(0);
+            load_k(stream, a.kpool + base_n);
+            __builtin_amdgcn_sched_barrier(0);
+            bf16x8 pf[RT];
+            float alpha[RT];
+            softmax(s, t0, pf, alpha);
+            accumulate(pf, alpha);
+            __builtin_amdgcn_sched_barrier(0);
+            load_v(stream, a.vpool + base_n);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    if (p.stream_loads) block_loop(std::true_type{});       // uniform: one of two copies of the loop runs
+    else block_loop(std::false_type{});
 
     // results: O^T tile lane (c, g) holds head dims dt*16 + 4g..4g+3 of row (rt, c)
 #pragma unroll

@@ -199,6 +199,8 @@ struct AttnPhase {
     int causal_pos0, causal_stride;  // query token i of a unit sees tokens t <= causal_pos0 + i*causal_stride
     int n_splits, split_tokens;      // split s covers [t_begin + s*split_tokens, ...) (multiples of 32)
     int rt;              // row tiles per item (1 or 2)
+    int stream_loads;    // 1: no other work item of the launch reads this phase's tokens; fetch them with the
+                         // non-temporal hint
     // Units of unequal size (a group some of whose members have left the batch): unit u owns query tokens
     // unit_row0[u] .. unit_row0[u] + unit_count[u] - 1 (count <= q_per_unit) and its pages are those of row
     // unit_row0[u]; row_unit[token] is the unit of a query token.  All three null: unit u owns tokens
