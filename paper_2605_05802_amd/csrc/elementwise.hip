@@ -7,29 +7,36 @@
 namespace sr {
 namespace {
 
-// deterministic block-wide sum over 512 threads
-__device__ __forceinline__ float block_sum_512(float v, float *s_red) {
+// deterministic block-wide sums of ROWS values over 512 threads (the same order of additions for every row)
+template <int ROWS>
+__device__ __forceinline__ void block_sums_512(float (&v)[ROWS], float (*s_red)[8]) {
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) v += __shfl_xor(v, off, 64);
+    for (int r = 0; r < ROWS; ++r)
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) v[r] += __shfl_xor(v[r], off, 64);
     const int wave = threadIdx.x >> 6;
-    if ((threadIdx.x & 63) == 0) s_red[wave] = v;
+    if ((threadIdx.x & 63) == 0) {
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) s_red[r][wave] = v[r];
+    }
     __syncthreads();
-    const float total = ((s_red[0] + s_red[1]) + (s_red[2] + s_red[3])) + ((s_red[4] + s_red[5]) + (s_red[6] + s_red[7]));
-    __syncthreads();
-    return total;
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r)
+        v[r] = ((s_red[r][0] + s_red[r][1]) + (s_red[r][2] + s_red[r][3])) + ((s_red[r][4] + s_red[r][5]) + (s_red[r][6] + s_red[r][7]));
 }
 
 // x = resid (+ partials) or embedding row; resid <- x (if write_resid); out <- bf16(x * rsqrt(mean(x^2)+eps) * gain)
-// H <= 8192: each thread keeps its (at most 2 x 8) values in registers between the two passes.
-template <bool F32OUT>
+// H <= 8192: each thread keeps its (at most 2 x 8) values per row in registers between the two passes.
+// A workgroup takes ROWS consecutive output rows and requests all of their data before the first reduction:
+// one row at decode time (few rows, every compute unit should get one), four for prefill-sized batches, where
+// a row's three dependent memory round trips would otherwise leave the memory system mostly idle.  The
+// arithmetic of a row does not depend on ROWS.
+template <bool F32OUT, int ROWS>
 __global__ __launch_bounds__(512) void resid_norm_kernel(NormArgs a) {
-    __shared__ float s_red[8];
-    const int m = blockIdx.x;
-    const size_t row = (size_t)(m / a.src_dup) * a.src_stride + a.src_off;
-    float *x = a.resid + row * a.H;
+    __shared__ float s_red[ROWS][8];
     const int nvec = a.H >> 3;                       // groups of 8 consecutive features
-    float xv[2][8];
-    float ss = 0.f;
+    float xv[ROWS][2][8];
+    float ss[ROWS];
     // the gains do not depend on the reduction: fetch them first, so that the second pass starts from registers
     uint4 graw[2];
 #pragma unroll
@@ -38,78 +45,91 @@ __global__ __launch_bounds__(512) void resid_norm_kernel(NormArgs a) {
         graw[it] = v < nvec ? *(const uint4 *)(a.gain + v * 8) : make_uint4(0, 0, 0, 0);
     }
 
-    const uint16_t *e = nullptr;
-    if (a.embed) {
-        const int tok = a.tokens[(size_t)(m / a.tok_chunk) * a.tok_stride + a.tok_off + m % a.tok_chunk];
-        e = a.embed + (size_t)tok * a.H;
-    }
 #pragma unroll
-    for (int it = 0; it < 2; ++it) {
-        const int v = threadIdx.x + it * 512;
-        if (v < nvec) {
-            float *f = xv[it];
-            if (e) {
-                const uint4 raw = *(const uint4 *)(e + v * 8);
-                const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+    for (int r = 0; r < ROWS; ++r) {
+        const int m = blockIdx.x * ROWS + r;
+        ss[r] = 0.f;
+        if (m >= a.rows_out) continue;               // uniform across the workgroup
+        const size_t row = (size_t)(m / a.src_dup) * a.src_stride + a.src_off;
+        float *x = a.resid + row * a.H;
+        const uint16_t *e = nullptr;
+        if (a.embed) {
+            const int tok = a.tokens[(size_t)(m / a.tok_chunk) * a.tok_stride + a.tok_off + m % a.tok_chunk];
+            e = a.embed + (size_t)tok * a.H;
+        }
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    f[2 * i] = __uint_as_float(w[i] << 16);
-                    f[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
-                }
-            } else {
-                f32x4 lo = *(const f32x4 *)(x + v * 8), hi = *(const f32x4 *)(x + v * 8 + 4);
-                const float *p0 = a.partials + row * a.H + v * 8;
-                int s = 0;
-                for (; s + 4 <= a.n_partials; s += 4) {          // four independent loads in flight,
-                    f32x4 pl[4], ph[4];                          // added in split order
+        for (int it = 0; it < 2; ++it) {
+            const int v = threadIdx.x + it * 512;
+            if (v < nvec) {
+                float *f = xv[r][it];
+                if (e) {
+                    const uint4 raw = *(const uint4 *)(e + v * 8);
+                    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const float *p = p0 + (size_t)(s + u) * a.partial_stride;
-                        pl[u] = *(const f32x4 *)p;
-                        ph[u] = *(const f32x4 *)(p + 4);
+                    for (int i = 0; i < 4; ++i) {
+                        f[2 * i] = __uint_as_float(w[i] << 16);
+                        f[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u);
+                    }
+                } else {
+                    f32x4 lo = *(const f32x4 *)(x + v * 8), hi = *(const f32x4 *)(x + v * 8 + 4);
+                    const float *p0 = a.partials + row * a.H + v * 8;
+                    int s = 0;
+                    for (; s + 4 <= a.n_partials; s += 4) {          // four independent loads in flight,
+                        f32x4 pl[4], ph[4];                          // added in split order
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) {
+                            const float *p = p0 + (size_t)(s + u) * a.partial_stride;
+                            pl[u] = *(const f32x4 *)p;
+                            ph[u] = *(const f32x4 *)(p + 4);
+                        }
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) { lo += pl[u]; hi += ph[u]; }
+                    }
+                    for (; s < a.n_partials; ++s) {
+                        const float *p = p0 + (size_t)s * a.partial_stride;
+                        lo += *(const f32x4 *)p;
+                        hi += *(const f32x4 *)(p + 4);
                     }
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) { lo += pl[u]; hi += ph[u]; }
-                }
-                for (; s < a.n_partials; ++s) {
-                    const float *p = p0 + (size_t)s * a.partial_stride;
-                    lo += *(const f32x4 *)p;
-                    hi += *(const f32x4 *)(p + 4);
+                    for (int i = 0; i < 4; ++i) { f[i] = lo[i]; f[4 + i] = hi[i]; }
                 }
 #pragma unroll
-                for (int i = 0; i < 4; ++i) { f[i] = lo[i]; f[4 + i] = hi[i]; }
-            }
-#pragma unroll
-            for (int i = 0; i < 8; ++i) ss += f[i] * f[i];
-            if (a.write_resid) {
-                *(f32x4 *)(x + v * 8) = f32x4{f[0], f[1], f[2], f[3]};
-                *(f32x4 *)(x + v * 8 + 4) = f32x4{f[4], f[5], f[6], f[7]};
+                for (int i = 0; i < 8; ++i) ss[r] += f[i] * f[i];
+                if (a.write_resid) {
+                    *(f32x4 *)(x + v * 8) = f32x4{f[0], f[1], f[2], f[3]};
+                    *(f32x4 *)(x + v * 8 + 4) = f32x4{f[4], f[5], f[6], f[7]};
+                }
             }
         }
     }
-    const float total = block_sum_512(ss, s_red);
-    const float inv = 1.0f / sqrtf(total / (float)a.H + a.eps);
+    block_sums_512<ROWS>(ss, s_red);
 
 #pragma unroll
-    for (int it = 0; it < 2; ++it) {
-        const int v = threadIdx.x + it * 512;
-        if (v < nvec) {
-            const float *f = xv[it];
-            const uint32_t gw[4] = {graw[it].x, graw[it].y, graw[it].z, graw[it].w};
-            float y[8];
+    for (int r = 0; r < ROWS; ++r) {
+        const int m = blockIdx.x * ROWS + r;
+        if (m >= a.rows_out) continue;
+        const float inv = 1.0f / sqrtf(ss[r] / (float)a.H + a.eps);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                y[2 * i] = f[2 * i] * inv * __uint_as_float(gw[i] << 16);
-                y[2 * i + 1] = f[2 * i + 1] * inv * __uint_as_float(gw[i] & 0xFFFF0000u);
-            }
-            if constexpr (F32OUT) {
-                float *dst = a.out32 + (size_t)m * a.H + v * 8;
-                *(f32x4 *)dst = f32x4{y[0], y[1], y[2], y[3]};
-                *(f32x4 *)(dst + 4) = f32x4{y[4], y[5], y[6], y[7]};
-            } else {
-                uint4 o = make_uint4(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]), pack_bf16x2(y[4], y[5]),
-                                     pack_bf16x2(y[6], y[7]));
-                *(uint4 *)((uint16_t *)a.out + frag_offset(m, v * 8, a.mt_total)) = o;
+        for (int it = 0; it < 2; ++it) {
+            const int v = threadIdx.x + it * 512;
+            if (v < nvec) {
+                const float *f = xv[r][it];
+                const uint32_t gw[4] = {graw[it].x, graw[it].y, graw[it].z, graw[it].w};
+                float y[8];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    y[2 * i] = f[2 * i] * inv * __uint_as_float(gw[i] << 16);
+                    y[2 * i + 1] = f[2 * i + 1] * inv * __uint_as_float(gw[i] & 0xFFFF0000u);
+                }
+                if constexpr (F32OUT) {
+                    float *dst = a.out32 + (size_t)m * a.H + v * 8;
+                    *(f32x4 *)dst = f32x4{y[0], y[1], y[2], y[3]};
+                    *(f32x4 *)(dst + 4) = f32x4{y[4], y[5], y[6], y[7]};
+                } else {
+                    uint4 o = make_uint4(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]), pack_bf16x2(y[4], y[5]),
+                                         pack_bf16x2(y[6], y[7]));
+                    *(uint4 *)((uint16_t *)a.out + frag_offset(m, v * 8, a.mt_total)) = o;
+                }
             }
         }
     }
@@ -283,8 +303,9 @@ __global__ void copy_page_kernel(uint4 *kpool, uint4 *vpool, size_t layer_vec, s
 int launch_resid_norm(const NormArgs &a, hipStream_t stream) {
     if (a.rows_out <= 0) return SR_OK;
     if (a.H % 8 || a.H > 8192) return SR_E_ARG;
-    if (a.out32) resid_norm_kernel<true><<<dim3(a.rows_out), dim3(512), 0, stream>>>(a);
-    else resid_norm_kernel<false><<<dim3(a.rows_out), dim3(512), 0, stream>>>(a);
+    if (a.out32) resid_norm_kernel<true, 1><<<dim3(a.rows_out), dim3(512), 0, stream>>>(a);
+    else if (a.rows_out >= 2048) resid_norm_kernel<false, 4><<<dim3(ceil_div(a.rows_out, 4)), dim3(512), 0, stream>>>(a);
+    else resid_norm_kernel<false, 1><<<dim3(a.rows_out), dim3(512), 0, stream>>>(a);
     SR_HIP(hipGetLastError());
     return SR_OK;
 }
