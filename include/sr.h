@@ -386,6 +386,17 @@ int sr_profile_read(sr_ctx *ctx, sr_kernel_time *host_out /* [SR_KC_COUNT] */, v
 int sr_probe_hbm(const void *src, void *dst, size_t bytes, int mode, int iters, void *stream, double *host_GBs);
 int sr_probe_mfma_bf16(void *scratch, size_t scratch_bytes, int iters, void *stream, double *host_TFLOPs);
 
+/*
+ * One layer's decode attention launch at the 7B attention shape (28 query / 4 kv heads of 128, 64-token pages) on
+ * synthetic pages, for studying its phases apart: phases = 1 the shared-prompt phase alone (one unit per group, the
+ * members' query rows batched over each prompt block), 2 the private phase alone (one unit per sequence, priv_splits
+ * splits of priv_tokens tokens), 3 both in one launch as sr_decode_step runs them.  hot != 0: every page-table entry
+ * names one of a few pages, so all K/V loads are cache hits.  Allocates and frees its own buffers, waits for the
+ * stream, and writes the mean launch duration in microseconds and the K/V bytes one launch has to read to HOST doubles.
+ */
+int sr_probe_decode_attention(int n_groups, int G, int shared_tokens, int priv_tokens, int priv_splits, int phases,
+                              int hot, int iters, void *stream, double *host_us, double *host_kv_bytes);
+
 /* Text for a status code; for SR_E_HIP the text of the last HIP error seen by this thread. */
 const char *sr_strerror(int status);
 

@@ -20,7 +20,8 @@ EXPORTS = ("sr_init", "sr_destroy", "sr_load_weights", "sr_prefill_chunk", "sr_d
            "sr_retire_and_compact", "sr_gate_batch", "sr_set_actions", "sr_get_actions", "sr_get_logits",
            "sr_get_live_map", "sr_stats", "sr_strerror", "sr_profile", "sr_profile_read", "sr_signals_batch",
            "sr_score_chunk", "sr_get_logprob", "sr_grpo_loss", "sr_finish_sequences", "sr_grpo_loss_static",
-           "sr_probe_hbm", "sr_probe_mfma_bf16", "sr_gate_batch_antidiag")
+           "sr_probe_hbm", "sr_probe_mfma_bf16", "sr_gate_batch_antidiag",
+           "sr_probe_decode_attention")
 
 KERNEL_CLASSES = ("norm", "gemm_qkv", "qkv_post", "attn_decode", "attn_prefill", "attn_merge",
                   "gemm_o", "gemm_gate_up", "gemm_down", "gemm_lm_head", "argmax")
@@ -96,6 +97,8 @@ def lib():
         L.sr_grpo_loss.argtypes = [vp, vp, ci, ci, ctypes.c_double, vp, vp, vp, vp]
         L.sr_grpo_loss_static.argtypes = [vp, vp, ci, ci, ctypes.c_double, vp, vp, vp]
         L.sr_probe_hbm.argtypes = [vp, vp, ctypes.c_size_t, ci, ci, vp, ctypes.POINTER(ctypes.c_double)]
+        L.sr_probe_decode_attention.argtypes = [ci] * 8 + [vp, ctypes.POINTER(ctypes.c_double),
+                                                  ctypes.POINTER(ctypes.c_double)]
         L.sr_probe_mfma_bf16.argtypes = [vp, ctypes.c_size_t, ci, vp, ctypes.POINTER(ctypes.c_double)]
         L.sr_finish_sequences.argtypes = [vp, vp, ctypes.POINTER(ci), vp]
         L.sr_set_actions.argtypes = [vp, ci, vp, vp]
@@ -192,6 +195,16 @@ def sr_probe_hbm(src, dst, mode: int, iters: int = 10, stream=None) -> float:
     _check(lib().sr_probe_hbm(_ptr(src), _ptr(dst), nbytes, mode, iters, _stream(stream), ctypes.byref(out)),
            "sr_probe_hbm")
     return out.value
+
+
+def sr_probe_decode_attention(n_groups: int, G: int, shared_tokens: int, priv_tokens: int, priv_splits: int,
+                              phases: int, hot: bool = False, iters: int = 24, stream=None):
+    """(microseconds per launch, K/V bytes per launch) of one layer's decode attention on synthetic pages."""
+    us, nbytes = ctypes.c_double(), ctypes.c_double()
+    _check(lib().sr_probe_decode_attention(n_groups, G, shared_tokens, priv_tokens, priv_splits, phases, int(hot), iters,
+                                           _stream(stream), ctypes.byref(us), ctypes.byref(nbytes)),
+           "sr_probe_decode_attention")
+    return us.value, nbytes.value
 
 
 def sr_probe_mfma_bf16(scratch, iters: int = 3, stream=None) -> float:

@@ -2,6 +2,7 @@
 // read, a plain copy and a register-resident bf16 matrix-core loop achieve, next to the published peaks.
 // Auxiliaries of the boundary (sr_probe_*); nothing on the rollout path calls them.
 #include <functional>
+#include <vector>
 
 #include "sr_internal.h"
 
@@ -119,4 +120,97 @@ extern "C" int sr_probe_mfma_bf16(void *scratch, size_t scratch_bytes, int iters
     const double flop = (double)wgs * 4 * inner * 4 * 2.0 * 32 * 32 * 16;
     *host_TFLOPs = flop / (ms * 1e-3) / 1e12;
     return SR_OK;
+}
+
+// The decode attention launch of one layer on synthetic pages, for studying its two phases apart: the shared-prompt
+// phase (one unit per group, the members' query rows batched), the private phase (one unit per sequence), or both in
+// one launch as the decode step does.  hot != 0 maps every page-table entry to the same few pages, so that all K/V
+// loads hit in the caches and what is left is the kernel's own instruction and latency chain.
+extern "C" int sr_probe_decode_attention(int n_groups, int G, int shared_tokens, int priv_tokens, int priv_splits,
+                                         int phases, int hot, int iters, void *stream, double *host_us,
+                                         double *host_kv_bytes) {
+    const int n_q = 28, n_kv = 4, d = 128, page_tokens = 64, n_rep = n_q / n_kv, NL = 6;   // the 7B attention shape
+    if (n_groups < 1 || G < 2 || G > 16 || shared_tokens < 0 || shared_tokens % page_tokens || priv_tokens < 1 ||
+        priv_splits < 1 || priv_splits > 16 || phases < 1 || phases > 3 || iters < 1 || !host_us)
+        return SR_E_ARG;
+    if ((phases & 1) && shared_tokens == 0) return SR_E_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    const int M = n_groups * G;
+    const int shared_pages = shared_tokens / page_tokens, priv_pages = ceil_div(priv_tokens, page_tokens);
+    const int max_pages = shared_pages + priv_pages;
+    const int n_pages = n_groups * shared_pages + M * priv_pages;
+    const size_t layer_elems = (size_t)n_pages * n_kv * page_tokens * d;
+    // NL layers' worth of pages are rotated through so that consecutive launches do not find their data in a cache
+    uint16_t *kp = nullptr, *vp = nullptr, *q = nullptr;
+    int32_t *dpt = nullptr;
+    float *po = nullptr, *pml = nullptr;
+    std::vector<int32_t> pt((size_t)M * max_pages);
+    for (int u = 0; u < M; ++u)
+        for (int j = 0; j < max_pages; ++j) {
+            int page = j < shared_pages ? (u / G) * shared_pages + j : n_groups * shared_pages + (j - shared_pages) * M + u;
+            if (hot) page = j < shared_pages ? j % 4 : 4 + (j & 1);
+            pt[(size_t)u * max_pages + j] = page;
+        }
+    AttnPhase x{}, y{};
+    const int ctx = shared_tokens + priv_tokens;
+    x.n_units = n_groups; x.q_per_unit = G; x.rt = 1;
+    x.q_per_item = 16 / n_rep < G ? 16 / n_rep : G;
+    x.items_per_unit = ceil_div(G, x.q_per_item);
+    x.pt_row_stride = G; x.t_begin = 0; x.t_end = shared_tokens; x.causal_pos0 = ctx - 1;
+    x.n_splits = shared_tokens ? ceil_div(shared_tokens, 256) : 1;
+    if (x.n_splits > 16) x.n_splits = 16;
+    x.split_tokens = shared_tokens ? round_up(ceil_div(shared_tokens, x.n_splits), 32) : 32;
+    y.n_units = M; y.q_per_unit = 1; y.q_per_item = 1; y.items_per_unit = 1; y.rt = 1; y.pt_row_stride = 1;
+    y.t_begin = shared_tokens; y.t_end = ctx; y.causal_pos0 = ctx - 1;
+    y.n_splits = priv_splits; y.split_tokens = round_up(ceil_div(priv_tokens, priv_splits), 32);
+    y.stream_loads = priv_tokens >= 512;
+    const size_t items0 = (size_t)x.n_units * n_kv * x.items_per_unit * x.n_splits, items1 = (size_t)M * n_kv * y.n_splits;
+    int rc = SR_OK;
+    auto fail = [&](hipError_t e, const char *what) { note_hip_error(e, what); rc = SR_E_HIP; };
+    hipError_t e;
+    if ((e = hipMalloc(&kp, layer_elems * 2 * NL)) != hipSuccess) fail(e, "hipMalloc");
+    if (rc == SR_OK && (e = hipMalloc(&vp, layer_elems * 2 * NL)) != hipSuccess) fail(e, "hipMalloc");
+    if (rc == SR_OK && (e = hipMalloc(&q, (size_t)M * n_q * d * 2)) != hipSuccess) fail(e, "hipMalloc");
+    if (rc == SR_OK && (e = hipMalloc(&dpt, pt.size() * 4)) != hipSuccess) fail(e, "hipMalloc");
+    if (rc == SR_OK && (e = hipMalloc(&po, (items0 + items1) * 16 * d * 4)) != hipSuccess) fail(e, "hipMalloc");
+    if (rc == SR_OK && (e = hipMalloc(&pml, (items0 + items1) * 16 * 2 * 4)) != hipSuccess) fail(e, "hipMalloc");
+    if (rc == SR_OK) {
+        (void)hipMemsetAsync(kp, 0x11, layer_elems * 2 * NL, st);      // small finite bf16 values
+        (void)hipMemsetAsync(vp, 0x11, layer_elems * 2 * NL, st);
+        (void)hipMemsetAsync(q, 0x11, (size_t)M * n_q * d * 2, st);
+        if ((e = hipMemcpy(dpt, pt.data(), pt.size() * 4, hipMemcpyHostToDevice)) != hipSuccess) fail(e, "hipMemcpy");
+    }
+    if (rc == SR_OK) {
+        x.part_o = po; x.part_ml = pml;
+        y.part_o = po + items0 * 16 * d; y.part_ml = pml + items0 * 16 * 2;
+        AttnArgs a{};
+        a.q = q; a.page_table = dpt; a.pt_stride = max_pages; a.page_tokens = page_tokens;
+        a.n_q = n_q; a.n_kv = n_kv; a.d = d; a.scale = 0.0883883f;
+        AttnPhase ph[2] = {x, y};
+        const AttnPhase *first = phases == 2 ? ph + 1 : ph;
+        const int n_ph = phases == 3 ? 2 : 1;
+        int layer = 0;
+        double ms = 0;
+        int lrc = SR_OK;
+        rc = time_launches(st, iters, &ms, [&] {
+            a.kpool = kp + (size_t)(layer % NL) * layer_elems;
+            a.vpool = vp + (size_t)(layer % NL) * layer_elems;
+            ++layer;
+            const int r = launch_attention(a, first, n_ph, st);
+            if (r != SR_OK) lrc = r;
+        });
+        if (rc == SR_OK) rc = lrc;
+        *host_us = ms * 1e3;
+        if (host_kv_bytes)
+            *host_kv_bytes = 2.0 * n_kv * d * 2 * (((phases & 1) ? (double)n_groups * shared_tokens : 0.0) +
+                                                    ((phases & 2) ? (double)M * priv_tokens : 0.0));
+    }
+    (void)hipStreamSynchronize(st);
+    if (kp) (void)hipFree(kp);
+    if (vp) (void)hipFree(vp);
+    if (q) (void)hipFree(q);
+    if (dpt) (void)hipFree(dpt);
+    if (po) (void)hipFree(po);
+    if (pml) (void)hipFree(pml);
+    return rc;
 }
