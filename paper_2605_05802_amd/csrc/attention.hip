@@ -251,6 +251,209 @@ __global__ __launch_bounds__(256, RT == 1 ? 3 : 2) void attn_kernel(AttnArgs a, 
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Prefill attention: the four work items of a workgroup are four consecutive query tiles of one
+// (unit, kv head) and need the same K/V blocks, so a block goes from global memory to LDS once per
+// workgroup (each thread copies its 16-byte slots, one block ahead, through registers) and every
+// wavefront takes its MFMA operands from LDS: a quarter of the vector-memory traffic of the kernel
+// above, which at a context of thousands of tokens is bound by what L2 can deliver.  Two LDS buffers,
+// one workgroup barrier per block.  One split, one phase: the normalised output is written directly.
+// ---------------------------------------------------------------------------------------------
+template <int D, int RT>
+__global__ __launch_bounds__(256, 2) void attn_prefill_shared_kernel(AttnArgs a, AttnPhase p) {
+    constexpr int KS = D / 32, DT = D / 16;
+    constexpr int SLOTS = 32 * D / 8;              // 16-byte slots of one K (or V) block
+    constexpr int NS = SLOTS / 256;                // slots per thread
+    __shared__ u32x4 lds[2][2][SLOTS];             // [buffer][K, V][slot]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+    const int groups_per_unit = (p.items_per_unit + 3) >> 2;
+    int rest = blockIdx.x;
+    const int qg = rest % groups_per_unit; rest /= groups_per_unit;
+    const int kvh = rest % a.n_kv;
+    const int unit = rest / a.n_kv;
+    const int qtile = qg * 4 + wave;               // beyond items_per_unit: this wavefront only helps with the copies
+    const int n_rep = a.n_q / a.n_kv;
+
+    const int c = lane & 15, g = lane >> 4;
+    const int u_row0 = p.unit_row0 ? p.unit_row0[unit] : unit * p.q_per_unit;
+    const int u_count = p.unit_count ? p.unit_count[unit] : p.q_per_unit;
+    const int32_t *pt = a.page_table + (size_t)(p.unit_row0 ? u_row0 : unit * p.pt_row_stride) * a.pt_stride;
+    const int blocks_per_page = a.page_tokens >> 5;
+    auto block_base = [&](int t0) -> size_t {
+        const int page = pt[t0 / a.page_tokens];
+        const int blk = (t0 % a.page_tokens) >> 5;
+        return (((size_t)page * a.n_kv + kvh) * blocks_per_page + blk) * (size_t)(32 * D);
+    };
+
+    bf16x8 qf[RT][KS];
+    int limit[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        const int row = rt * 16 + c;
+        const int qi = qtile * p.q_per_item + row / n_rep;
+        const int hr = row % n_rep;
+        const bool used = qtile < p.items_per_unit && (row < p.q_per_item * n_rep) && (qi < u_count);
+        limit[rt] = used ? p.causal_pos0 + qi * p.causal_stride : -1;
+        const uint16_t *qp = a.q + (((size_t)u_row0 + qi) * a.n_q + kvh * n_rep + hr) * D + 8 * g;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            uint4 raw = make_uint4(0, 0, 0, 0);
+            if (used) raw = *(const uint4 *)(qp + ks * 32);
+            qf[rt][ks] = __builtin_bit_cast(bf16x8, raw);
+        }
+    }
+    int max_limit = -1, min_limit = 0x7FFFFFFF;      // over the used rows of this wavefront
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        max_limit = max(max_limit, limit[rt]);
+        min_limit = min(min_limit, limit[rt] < 0 ? 0x7FFFFFFF : limit[rt]);
+    }
+#pragma unroll
+    for (int off = 1; off < 16; off <<= 1) {
+        max_limit = max(max_limit, __shfl_xor(max_limit, off, 64));
+        min_limit = min(min_limit, __shfl_xor(min_limit, off, 64));
+    }
+    // tokens below t_vis are visible to every used row (unused rows hold zero queries and are never written out)
+    const int t_vis = __builtin_amdgcn_readfirstlane(min_limit == 0x7FFFFFFF ? 0 : min_limit + 1);
+    // this wavefront's range, and the workgroup's: its last query token sees the most
+    const int t_hi = __builtin_amdgcn_readfirstlane(min(p.t_end, max_limit + 1));
+    const int last_q = min((qg * 4 + 4) * p.q_per_item, u_count) - 1;
+    const int t_hi_wg = min(p.t_end, p.causal_pos0 + last_q * p.causal_stride + 1);
+    const int n_blocks = (t_hi_wg - p.t_begin + 31) >> 5;          // t_begin is a multiple of 32
+
+    f32x4 o[DT][RT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) o[dt][rt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float mrun[RT], lrun[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) { mrun[rt] = kNegBig; lrun[rt] = 0.f; }
+    const float scale_log2 = a.scale * 1.4426950408889634f;
+
+    u32x4 sk[NS], sv[NS];                           // this thread's slots of the block being brought in
+    auto fetch = [&](int blk) {
+        const size_t base = block_base(p.t_begin + 32 * blk);
+        const u32x4 *ksrc = (const u32x4 *)(a.kpool + base), *vsrc = (const u32x4 *)(a.vpool + base);
+#pragma unroll
+        for (int i = 0; i < NS; ++i) { sk[i] = ksrc[tid + 256 * i]; sv[i] = vsrc[tid + 256 * i]; }
+    };
+    auto stash = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < NS; ++i) { lds[buf][0][tid + 256 * i] = sk[i]; lds[buf][1][tid + 256 * i] = sv[i]; }
+    };
+
+    if (n_blocks > 0) {
+        fetch(0);
+        stash(0);
+        __syncthreads();
+        if (n_blocks > 1) fetch(1);
+    }
+    for (int blk = 0; blk < n_blocks; ++blk) {
+        const int buf = blk & 1;
+        const int t0 = p.t_begin + 32 * blk;
+        if (t0 < t_hi) {                            // uniform per wavefront: later blocks are invisible to all its rows
+            const u32x4 *kb = lds[buf][0], *vb = lds[buf][1];
+            f32x4 s[RT][2];
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                for (int tt = 0; tt < 2; ++tt) s[rt][tt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            // k-steps outermost: 2 x RT independent accumulators take turns, so an MFMA never waits for the one before it
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                for (int tt = 0; tt < 2; ++tt) {
+                    const bf16x8 kf = __builtin_bit_cast(bf16x8, kb[(ks * 32 + tt * 16 + c) * 4 + g]);
+#pragma unroll
+                    for (int rt = 0; rt < RT; ++rt)
+                        s[rt][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[rt][ks], s[rt][tt], 0, 0, 0);
+                }
+            bf16x8 pf[RT];
+            float alpha[RT];
+            // Online softmax.  A block that every used row sees entirely (all but the last one or two of a range)
+            // skips the per-token visibility tests; the exponentials are the hardware's base-2 exponential as it is
+            // (arguments <= 0; results below 2^-126 of the row maximum may flush to zero).
+            auto softmax = [&](auto masked) __attribute__((always_inline)) {
+                constexpr bool MASKED = decltype(masked)::value;
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt) {
+                    const int lim = min(limit[rt], t_hi - 1);
+                    float bmax = kNegBig;
+                    bool ok[2][4];
+#pragma unroll
+                    for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            ok[tt][e] = !MASKED || (t0 + tt * 16 + 4 * g + e) <= lim;
+                            s[rt][tt][e] = ok[tt][e] ? s[rt][tt][e] * scale_log2 : kNegBig;
+                            bmax = fmaxf(bmax, s[rt][tt][e]);
+                        }
+                    bmax = fmaxf(bmax, __shfl_xor(bmax, 16, 64));
+                    bmax = fmaxf(bmax, __shfl_xor(bmax, 32, 64));
+                    const float mnew = fmaxf(mrun[rt], bmax);
+                    alpha[rt] = __builtin_amdgcn_exp2f(mrun[rt] - mnew);
+                    mrun[rt] = mnew;
+                    float psum = 0.f;
+                    float pv[8];
+#pragma unroll
+                    for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float pe = ok[tt][e] ? __builtin_amdgcn_exp2f(s[rt][tt][e] - mnew) : 0.f;
+                            pv[tt * 4 + e] = pe;
+                            psum += pe;
+                        }
+                    lrun[rt] = lrun[rt] * alpha[rt] + psum;
+                    const uint4 praw = make_uint4(pack_bf16x2(pv[0], pv[1]), pack_bf16x2(pv[2], pv[3]),
+                                                  pack_bf16x2(pv[4], pv[5]), pack_bf16x2(pv[6], pv[7]));
+                    pf[rt] = __builtin_bit_cast(bf16x8, praw);
+                }
+            };
+            if (t0 + 32 <= t_vis && t0 + 32 <= t_hi) softmax(std::false_type{});
+            else softmax(std::true_type{});
+            // the accumulators are rescaled only when some row's maximum moved (after the first blocks it rarely does)
+            bool moved = false;
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) moved |= alpha[rt] != 1.0f;
+            const bool rescale = __any(moved);
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) {
+                const bf16x8 vf = __builtin_bit_cast(bf16x8, vb[(dt * 16 + c) * 4 + g]);
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt) {
+                    if (rescale) o[dt][rt] *= alpha[rt];
+                    o[dt][rt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[rt], o[dt][rt], 0, 0, 0);
+                }
+            }
+        }
+        if (blk + 1 < n_blocks) stash(buf ^ 1);     // the other buffer was last read before the previous barrier
+        __syncthreads();
+        if (blk + 2 < n_blocks) fetch(blk + 2);
+    }
+
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        float l = lrun[rt];
+        l += __shfl_xor(l, 16, 64);
+        l += __shfl_xor(l, 32, 64);
+        if (limit[rt] < 0) continue;
+        const int row = rt * 16 + c;
+        const size_t qtok = (size_t)u_row0 + qtile * p.q_per_item + row / n_rep;
+        const int col = (kvh * n_rep + row % n_rep) * D + 4 * g;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            float r[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) r[e] = l > 0.f ? o[dt][rt][e] / l : 0.f;
+            *(uint2 *)(a.direct_out + frag_offset((int)qtok, col + dt * 16, a.out_mt_total)) =
+                make_uint2(pack_bf16x2(r[0], r[1]), pack_bf16x2(r[2], r[3]));
+        }
+    }
+}
+
 struct MergeArgs {
     AttnPhase ph[2];
     int n_phases;
@@ -335,6 +538,19 @@ int launch_attention(const AttnArgs &a, const AttnPhase *phases, int n_phases, h
     if (n_items > 0x7FFFFFFF) return SR_E_ARG;
     const AttnPhase &p0 = phases[0], &p1 = phases[n_phases - 1];
     const int rt = p0.rt, n0 = (int)n[0], nt = (int)n_items;
+    if (a.direct_out && p0.items_per_unit >= 2) {
+        // prefill: the query tiles of a (unit, kv head) share their K/V blocks through LDS, four to a workgroup
+        const long long wgs = (long long)p0.n_units * a.n_kv * ((p0.items_per_unit + 3) / 4);
+        if (wgs > 0x7FFFFFFF) return SR_E_ARG;
+        dim3 sgrid((unsigned)wgs);
+        if (a.d == 128 && rt == 1) attn_prefill_shared_kernel<128, 1><<<sgrid, dim3(256), 0, stream>>>(a, p0);
+        else if (a.d == 128 && rt == 2) attn_prefill_shared_kernel<128, 2><<<sgrid, dim3(256), 0, stream>>>(a, p0);
+        else if (a.d == 64 && rt == 1) attn_prefill_shared_kernel<64, 1><<<sgrid, dim3(256), 0, stream>>>(a, p0);
+        else if (a.d == 64 && rt == 2) attn_prefill_shared_kernel<64, 2><<<sgrid, dim3(256), 0, stream>>>(a, p0);
+        else return SR_E_ARG;
+        SR_HIP(hipGetLastError());
+        return SR_OK;
+    }
     dim3 grid((unsigned)((n_items + 3) / 4)), block(256);
     if (a.d == 128 && rt == 1) attn_kernel<128, 1><<<grid, block, 0, stream>>>(a, p0, p1, n0, nt);
     else if (a.d == 128 && rt == 2) attn_kernel<128, 2><<<grid, block, 0, stream>>>(a, p0, p1, n0, nt);
