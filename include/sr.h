@@ -21,7 +21,10 @@
  *     scratch; they are released by sr_destroy.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls are
  *     asynchronous on that stream unless stated otherwise.  One context must be driven
- *     from one stream at a time.
+ *     from one stream at a time.  Page tables and row maps reach the device through pinned
+ *     staging slots guarded by events, so sr_prefill_chunk, sr_decode_step, sr_gate and
+ *     sr_finish_sequences do not wait for the stream; sr_retire_and_compact waits once, for
+ *     the retire mask (the page allocator lives on the host).
  *   - Batch rows are ordered group-major: while no sequence has finished early, live row r
  *     belongs to live group r / G, member r % G.  Retirement removes whole groups,
  *     sr_finish_sequences single members; both keep the order of the survivors
@@ -205,8 +208,8 @@ int sr_retire_and_compact(sr_ctx *ctx, int *host_n_live_groups, void *stream);
  * the shared prompt pages dropped; its action prefix is kept, because a later sr_gate still
  * compares it with the other members' (a pair is then divided by the longer of the two prefix
  * lengths, Section 3.2, and the member counts towards tau_K).  A group whose last member
- * finishes leaves the batch without being retired.  Rows keep their order; the sync point is
- * inside (page table and row maps are re-uploaded).  *host_n_live_seq (may be NULL) receives
+ * finishes leaves the batch without being retired.  Rows keep their order; page table and row
+ * maps are re-uploaded behind the work already queued.  *host_n_live_seq (may be NULL) receives
  * the number of sequences left.  SR_E_STATE: before the first turn, in the middle of one, or between
  * sr_gate and sr_retire_and_compact (the pending mask is indexed by the groups live at the gate).
  * After this call sr_gate writes to out_sums the plain sum of the pair distances.

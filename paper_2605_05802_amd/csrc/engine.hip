@@ -42,6 +42,48 @@ constexpr int kMaxAttnSplits = 16;
 
 using namespace sr;
 
+// Pinned host staging for small host-to-device uploads (page table, row maps): a ring of slots, each with an event
+// recorded behind its copy, so that an upload never blocks the host -- the host waits only if the copy that used a
+// slot four uploads ago has still not run.
+struct StagingRing {
+    static constexpr int kSlots = 4;
+    char *base = nullptr;
+    size_t slot_bytes = 0;
+    hipEvent_t ev[kSlots] = {};
+    bool busy[kSlots] = {};
+    int next = 0, cur = 0;
+
+    int init(size_t bytes) {
+        slot_bytes = (bytes + 255) & ~(size_t)255;
+        SR_HIP(hipHostMalloc((void **)&base, slot_bytes * kSlots, hipHostMallocDefault));
+        for (int i = 0; i < kSlots; ++i) SR_HIP(hipEventCreateWithFlags(&ev[i], hipEventDisableTiming));
+        return SR_OK;
+    }
+    void destroy() {
+        for (int i = 0; i < kSlots; ++i)
+            if (ev[i]) (void)hipEventDestroy(ev[i]);
+        if (base) (void)hipHostFree(base);
+        base = nullptr;
+    }
+    // the next slot, free to be written by the host
+    int acquire(void **p) {
+        cur = next;
+        next = (next + 1) % kSlots;
+        if (busy[cur]) {
+            SR_HIP(hipEventSynchronize(ev[cur]));
+            busy[cur] = false;
+        }
+        *p = base + (size_t)cur * slot_bytes;
+        return SR_OK;
+    }
+    // call right behind the copy that reads the slot handed out last
+    int commit(hipStream_t st) {
+        SR_HIP(hipEventRecord(ev[cur], st));
+        busy[cur] = true;
+        return SR_OK;
+    }
+};
+
 struct sr_ctx {
     sr_model_shape s{};
     sr_options o{};
@@ -66,9 +108,9 @@ struct sr_ctx {
     bool first_decode_of_turn = false, have_logits = false, gate_pending = false, pt_dirty = false;
     std::vector<int> live_orig_group;
     std::vector<std::vector<int>> pages;       // per live sequence
-    int32_t *h_pt = nullptr;                    // pinned staging [n_seq0][max_pages]
+    StagingRing pt_ring, rows_ring, units_ring, gate_ring;   // pinned staging of the uploads below
     uint8_t *h_retire = nullptr;                // pinned [n_groups0]
-    int32_t *h_rows = nullptr;                  // pinned [n_seq0]
+    int32_t *h_rows = nullptr;                  // current slot of rows_ring: [n_seq0]
 
     // groups some of whose members have finished (sr_finish_sequences)
     int n_rows = 0;                            // live sequences = rows of every per-sequence array
@@ -78,9 +120,9 @@ struct sr_ctx {
     std::vector<int> fin_index;                // by original id: row of its saved actions in d_fin_actions, or -1
     int n_finished = 0;
     bool irregular = false;                    // some live group has fewer than G live members
-    int32_t *h_units = nullptr;                // pinned [2 * n_groups0 + n_seq0]: unit_row0, unit_count, row_unit
+    int32_t *h_units = nullptr;                // current slot of units_ring [2 * n_groups0 + n_seq0]: unit_row0, unit_count, row_unit
     int32_t *d_units = nullptr;                // device copy
-    int32_t *h_gate_map = nullptr;             // pinned [2 * n_seq0]: source of every gate slot, its end step
+    int32_t *h_gate_map = nullptr;             // current slot of gate_ring [2 * n_seq0]: source of every gate slot, its end step
     int32_t *d_gate_map = nullptr;
     int32_t *d_fin_actions = nullptr;          // [n_seq0][max_turns]: action rows of finished members, in finishing order
     int32_t *d_gate_actions = nullptr;         // [n_groups0][G][max_turns]: gate input assembled from live and finished rows
@@ -221,14 +263,18 @@ int copy_vec(sr_ctx *c, uint16_t **dst, const void *src, size_t n, hipStream_t s
 int upload_page_table(sr_ctx *c, hipStream_t st) {
     if (!c->pt_dirty) return SR_OK;
     const int n = c->n_live_seq();
-    for (int r = 0; r < n; ++r) {
-        int32_t *row = c->h_pt + (size_t)r * c->max_pages;
-        const std::vector<int> &pg = c->pages[r];
-        for (size_t i = 0; i < pg.size(); ++i) row[i] = pg[i];
-    }
     if (n > 0) {
-        SR_HIP(hipMemcpyAsync(c->d_pt, c->h_pt, (size_t)n * c->max_pages * 4, hipMemcpyHostToDevice, st));
-        SR_HIP(hipStreamSynchronize(st));     // the staging buffer may be rewritten by the next call
+        int32_t *h_pt = nullptr;
+        SR_TRY(c->pt_ring.acquire((void **)&h_pt));
+        for (int r = 0; r < n; ++r) {
+            int32_t *row = h_pt + (size_t)r * c->max_pages;
+            const std::vector<int> &pg = c->pages[r];
+            size_t i = 0;
+            for (; i < pg.size(); ++i) row[i] = pg[i];
+            for (; i < (size_t)c->max_pages; ++i) row[i] = 0;
+        }
+        SR_HIP(hipMemcpyAsync(c->d_pt, h_pt, (size_t)n * c->max_pages * 4, hipMemcpyHostToDevice, st));
+        SR_TRY(c->pt_ring.commit(st));
     }
     c->pt_dirty = false;
     return SR_OK;
@@ -303,6 +349,7 @@ int grow_pages(sr_ctx *c, int new_len, bool shared, hipStream_t st) {
 int upload_units(sr_ctx *c, hipStream_t st) {
     c->irregular = false;
     int row = 0;
+    SR_TRY(c->units_ring.acquire((void **)&c->h_units));
     int32_t *row0 = c->h_units, *cnt = c->h_units + c->n_groups0, *ru = c->h_units + 2 * c->n_groups0;
     for (int g = 0; g < c->n_live_groups; ++g) {
         row0[g] = row;
@@ -314,7 +361,7 @@ int upload_units(sr_ctx *c, hipStream_t st) {
     if (c->irregular) {
         SR_HIP(hipMemcpyAsync(c->d_units, c->h_units, (size_t)(2 * c->n_groups0 + c->n_seq0) * 4,
                               hipMemcpyHostToDevice, st));
-        SR_HIP(hipStreamSynchronize(st));     // the staging buffer may be rewritten by the next call
+        SR_TRY(c->units_ring.commit(st));
     }
     return SR_OK;
 }
@@ -323,13 +370,13 @@ int upload_units(sr_ctx *c, hipStream_t st) {
 int compact_rows(sr_ctx *c, int n, hipStream_t st) {
     if (n <= 0) return SR_OK;
     SR_HIP(hipMemcpyAsync(c->d_rows, c->h_rows, (size_t)n * 4, hipMemcpyHostToDevice, st));
+    SR_TRY(c->rows_ring.commit(st));
     const int nxt = c->cur ^ 1;
     SR_TRY(launch_gather_rows(c->d_actions[nxt], c->d_actions[c->cur], c->d_rows, n, (size_t)c->o.max_turns * 4, st));
     SR_TRY(launch_gather_rows(c->d_logits[nxt], c->d_logits[c->cur], c->d_rows, n, (size_t)c->s.vocab * 4, st));
     SR_TRY(launch_gather_rows(c->d_orig[nxt], c->d_orig[c->cur], c->d_rows, n, 4, st));
     SR_TRY(launch_gather_rows(c->d_logprob[nxt], c->d_logprob[c->cur], c->d_rows, n, 8, st));
     c->cur = nxt;
-    SR_HIP(hipStreamSynchronize(st));         // h_rows may be rewritten by the next compaction
     return SR_OK;
 }
 
@@ -707,11 +754,11 @@ void sr_destroy(sr_ctx *c) {
     if (!c) return;
     (void)hipDeviceSynchronize();
     for (void *p : c->allocs) (void)hipFree(p);
-    if (c->h_pt) (void)hipHostFree(c->h_pt);
+    c->pt_ring.destroy();
+    c->rows_ring.destroy();
+    c->units_ring.destroy();
+    c->gate_ring.destroy();
     if (c->h_retire) (void)hipHostFree(c->h_retire);
-    if (c->h_rows) (void)hipHostFree(c->h_rows);
-    if (c->h_units) (void)hipHostFree(c->h_units);
-    if (c->h_gate_map) (void)hipHostFree(c->h_gate_map);
     for (auto &r : c->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
     for (hipEvent_t e : c->event_pool) (void)hipEventDestroy(e);
     delete c;
@@ -783,18 +830,17 @@ static int init_impl(sr_ctx *c) {
     for (int r = 0; r < c->n_seq0; ++r) c->row_orig[r] = r;
     c->end_step.assign(c->n_seq0, INT_MAX);
     c->fin_index.assign(c->n_seq0, -1);
-    SR_HIP(hipHostMalloc((void **)&c->h_units, (size_t)(2 * c->n_groups0 + c->n_seq0) * 4 + 16, hipHostMallocDefault));
-    SR_HIP(hipHostMalloc((void **)&c->h_gate_map, (size_t)2 * c->n_seq0 * 4 + 16, hipHostMallocDefault));
+    SR_TRY(c->units_ring.init((size_t)(2 * c->n_groups0 + c->n_seq0) * 4 + 16));
+    SR_TRY(c->gate_ring.init((size_t)2 * c->n_seq0 * 4 + 16));
     SR_TRY(dev_alloc(c, &c->d_units, (size_t)2 * c->n_groups0 + c->n_seq0));
     SR_TRY(dev_alloc(c, &c->d_gate_map, (size_t)2 * c->n_seq0));
     SR_TRY(dev_alloc(c, &c->d_fin_actions, (size_t)c->n_seq0 * o.max_turns));
     SR_TRY(dev_alloc(c, &c->d_gate_actions, (size_t)c->n_seq0 * o.max_turns));
     SR_TRY(dev_alloc(c, &c->d_gate_sig, (size_t)c->n_groups0));
     c->pages.assign(c->n_seq0, {});
-    SR_HIP(hipHostMalloc((void **)&c->h_pt, (size_t)c->n_seq0 * c->max_pages * 4 + 16, hipHostMallocDefault));
+    SR_TRY(c->pt_ring.init((size_t)c->n_seq0 * c->max_pages * 4 + 16));
     SR_HIP(hipHostMalloc((void **)&c->h_retire, c->n_groups0 + 16, hipHostMallocDefault));
-    SR_HIP(hipHostMalloc((void **)&c->h_rows, (size_t)c->n_seq0 * 4 + 16, hipHostMallocDefault));
-    memset(c->h_pt, 0, (size_t)c->n_seq0 * c->max_pages * 4);
+    SR_TRY(c->rows_ring.init((size_t)c->n_seq0 * 4 + 16));
     SR_TRY(dev_alloc(c, &c->d_pt, (size_t)c->n_seq0 * c->max_pages));
     SR_HIP(hipMemset(c->d_pt, 0, (size_t)c->n_seq0 * c->max_pages * 4));
     for (int i = 0; i < 2; ++i) {
@@ -1101,6 +1147,7 @@ int sr_gate(sr_ctx *c, int turn, int32_t *out_sums, uint8_t *out_retire, void *s
         // some members finished early: gather each group's G action rows (live rows and saved rows of
         // finished members, in member order) and evaluate d_K with per-pair longer-length normalisation,
         // and the termination-fraction clause when tau_H is set
+        SR_TRY(c->gate_ring.acquire((void **)&c->h_gate_map));
         int32_t *src = c->h_gate_map, *end = c->h_gate_map + c->n_seq0;
         int row = 0;
         for (int g = 0; g < ng; ++g) {
@@ -1117,7 +1164,7 @@ int sr_gate(sr_ctx *c, int turn, int32_t *out_sums, uint8_t *out_retire, void *s
             }
         }
         SR_HIP(hipMemcpyAsync(c->d_gate_map, c->h_gate_map, (size_t)2 * c->n_seq0 * 4, hipMemcpyHostToDevice, st));
-        SR_HIP(hipStreamSynchronize(st));     // the staging buffer may be rewritten by the next gate
+        SR_TRY(c->gate_ring.commit(st));
         SR_TRY(launch_assemble_gate(c->d_gate_map, c->d_actions[c->cur], c->d_fin_actions, ng * G, T,
                                     c->d_gate_actions, st));
         const int len1 = turn;
@@ -1137,6 +1184,7 @@ int sr_gate(sr_ctx *c, int turn, int32_t *out_sums, uint8_t *out_retire, void *s
 static int remove_rows(sr_ctx *c, const std::vector<char> &drop, int *freed, hipStream_t st) {
     const int ng = c->n_live_groups, n = c->n_rows;
     int kept_rows = 0, kept_groups = 0, row = 0;
+    SR_TRY(c->rows_ring.acquire((void **)&c->h_rows));
     for (int g = 0; g < ng; ++g) {
         int alive = 0;
         for (int m = 0; m < c->grp_count[g]; ++m, ++row) {
@@ -1206,20 +1254,23 @@ int sr_finish_sequences(sr_ctx *c, const uint8_t *host_done, int *host_n_live_se
     hipStream_t st = (hipStream_t)stream;
     const int n = c->n_rows;
     std::vector<char> drop(n, 0);
-    int n_done = 0;
+    std::vector<int> done_rows;
     for (int r = 0; r < n; ++r)
         if (host_done[r]) {
             drop[r] = 1;
-            c->h_rows[n_done++] = r;
+            done_rows.push_back(r);
         }
+    const int n_done = (int)done_rows.size();
     if (n_done > 0) {
         // keep the finished members' action rows: the gate of a later turn still compares their prefixes
+        SR_TRY(c->rows_ring.acquire((void **)&c->h_rows));
+        for (int i = 0; i < n_done; ++i) c->h_rows[i] = done_rows[i];
         SR_HIP(hipMemcpyAsync(c->d_rows, c->h_rows, (size_t)n_done * 4, hipMemcpyHostToDevice, st));
+        SR_TRY(c->rows_ring.commit(st));
         SR_TRY(launch_gather_rows(c->d_fin_actions + (size_t)c->n_finished * c->o.max_turns, c->d_actions[c->cur],
                                   c->d_rows, n_done, (size_t)c->o.max_turns * 4, st));
-        SR_HIP(hipStreamSynchronize(st));
         for (int i = 0; i < n_done; ++i) {
-            const int orig = c->row_orig[c->h_rows[i]];
+            const int orig = c->row_orig[done_rows[i]];
             c->end_step[orig] = c->turn;
             c->fin_index[orig] = c->n_finished++;
         }
