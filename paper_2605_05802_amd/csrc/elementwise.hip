@@ -135,11 +135,13 @@ __global__ __launch_bounds__(512) void resid_norm_kernel(NormArgs a) {
     }
 }
 
-// One 64-thread block per (row, group of heads).  A thread owns four consecutive dims i .. i+3 of the low half of
-// a head and their rotation partners i + d/2 .. (16-byte loads of the fp32 partials); d/8 threads make a head.
-__global__ __launch_bounds__(64) void qkv_post_kernel(QkvPostArgs a) {
+// One block per (row, group of heads): 64 threads at decode time, up to 640 (all heads of a row) for prefill-sized
+// batches, where tens of thousands of one-wavefront blocks would cost more than they move.  A thread owns four
+// consecutive dims i .. i+3 of the low half of a head and their rotation partners i + d/2 .. (16-byte loads of the
+// fp32 partials); d/8 threads make a head.
+__global__ __launch_bounds__(640) void qkv_post_kernel(QkvPostArgs a) {
     const int half = a.d >> 1, tph = half >> 2;               // threads per head
-    const int m = blockIdx.x, head = blockIdx.y * (64 / tph) + threadIdx.x / tph, i = (threadIdx.x % tph) * 4;
+    const int m = blockIdx.x, head = blockIdx.y * (blockDim.x / tph) + threadIdx.x / tph, i = (threadIdx.x % tph) * 4;
     if (head >= a.n_q + 2 * a.n_kv) return;
     const int unit = m / a.chunk, ci = m - unit * a.chunk;
     const int pos = a.pos0 + ci;
@@ -313,8 +315,14 @@ int launch_resid_norm(const NormArgs &a, hipStream_t stream) {
 int launch_qkv_post(const QkvPostArgs &a, hipStream_t stream) {
     if (a.rows <= 0) return SR_OK;
     if (a.d > 128 || a.d % 32 || a.rows > 0x7FFFFFF) return SR_E_ARG;
-    const int heads_per_block = 64 / (a.d / 8);                // d/8 threads per head
-    qkv_post_kernel<<<dim3(a.rows, ceil_div(a.n_q + 2 * a.n_kv, heads_per_block)), dim3(64), 0, stream>>>(a);
+    const int heads_per_wave = 64 / (a.d / 8);                 // d/8 threads per head
+    const int heads = a.n_q + 2 * a.n_kv;
+    int waves = 1;                                             // wavefronts per block
+    if (a.rows >= 2048) {
+        waves = ceil_div(heads, heads_per_wave);
+        if (waves > 10) waves = 10;
+    }
+    qkv_post_kernel<<<dim3(a.rows, ceil_div(heads, heads_per_wave * waves)), dim3(64 * waves), 0, stream>>>(a);
     SR_HIP(hipGetLastError());
     return SR_OK;
 }
