@@ -353,6 +353,23 @@ def test_mid_size_batch_takes_mixed_tiles_and_split_k():
     assert worst <= LOGIT_TOL and mism == 0
 
 
+def test_mid_size_batch_at_the_full_hidden_size():
+    """The same regime at the inner dimension of the 7B shape (hidden 3584, 28 query / 4 kv heads of 128, one layer):
+    384 rows per decode step, fewer after the gate, so the QKV, O and down projections run split along K = 3584 /
+    16896 on the tiled kernels and the gate|up projection on whole rounds of large tiles plus small ones; every logit
+    of every row against the checker, bound by the general rule (the contract mode on six sequences)."""
+    shape = synth.ModelShape(1, 3584, 28, 4, 128, 16896, 1024)
+    cfg = synth.EpisodeConfig("mid-3584", 48, 8, 8, 2, 2, 2, 64, (1,), 0.3, 0.4)
+    info = {}
+    rec, stats, worst, mism, near = run_and_compare(shape, cfg, seed=12, page_tokens=32, kv_pool_bytes=1 << 28,
+                                                     contract_rows=[0, 77, 150, 222, 301, 383], info=info)
+    tol = tolerance(info["contract_max"])
+    print(f"mid, hidden 3584: worst |dlogit| = {worst:.3e}, contract mode {info['contract_max']:.3e}, bound {tol:.3e}, "
+          f"mismatches = {mism}, near ties = {near}, rows after the gate = {stats['n_live_seq']}")
+    assert 128 < stats["n_live_seq"] < 384
+    assert worst <= tol and all(g < gap_rule(tol) for g in info["mismatch_gaps"])
+
+
 def test_7b_shape_sampled_sequences():
     """Full Qwen2.5-7B shape (28 layers, hidden 3584, 28q/4kv x 128, FFN 18944, vocab 152064) in the
     benchmark's launch configuration (16 groups x G=8 = 128 rows, 64-token pages).  The CPU checker
