@@ -462,14 +462,16 @@ struct MergeArgs {
     float *out32;       // non-null: row-major fp32 output instead of `out`
 };
 
-// One block per (query token, query head); thread = head dimension.  The (max, sum) pairs of all
-// partial results are fetched first, one per thread, and turned into weights; the weighted sum of
-// the partial outputs then runs over independent loads in a fixed order.
+// One block per (query token, query head); thread = head dimension.  The rows of all partial results are
+// worked out first; then the (max, sum) pairs, one per thread, and the first four partial outputs of every
+// thread are fetched in the same round trip, the pairs are turned into weights, and the weighted sum runs
+// over the items in a fixed order.
 constexpr int kMaxMergeItems = 64;
 
 __global__ __launch_bounds__(128) void attn_merge_kernel(MergeArgs a) {
     __shared__ float s_m[kMaxMergeItems], s_l[kMaxMergeItems], s_w[kMaxMergeItems];
     __shared__ unsigned s_row[kMaxMergeItems];      // partial-result row of each item
+    __shared__ const float *s_ml[kMaxMergeItems];   // its (max, sum) pair
     const int qt = blockIdx.x, h = blockIdx.y, dd = threadIdx.x;
     const int n_rep = a.n_q / a.n_kv;
     const int kvh = h / n_rep, hr = h % n_rep;
@@ -485,10 +487,19 @@ __global__ __launch_bounds__(128) void attn_merge_kernel(MergeArgs a) {
             const size_t prow = ((item0 + dd) * p.items_per_unit + qtile) * (16 * p.rt) + row;
             const size_t base = (size_t)(p.part_o - a.ph[0].part_o) / a.d;   // phases share one buffer
             s_row[n_items + dd] = (unsigned)(base + prow);
-            s_m[n_items + dd] = p.part_ml[prow * 2];
-            s_l[n_items + dd] = p.part_ml[prow * 2 + 1];
+            s_ml[n_items + dd] = p.part_ml + prow * 2;
         }
         n_items += p.n_splits;
+    }
+    __syncthreads();
+    const float *po = a.ph[0].part_o + (dd < a.d ? dd : 0);
+    float v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u] = u < n_items ? po[(size_t)s_row[u] * a.d] : 0.f;
+    if (dd < n_items) {
+        const float2 ml = *(const float2 *)s_ml[dd];
+        s_m[dd] = ml.x;
+        s_l[dd] = ml.y;
     }
     __syncthreads();
     float mbest = kNegBig;
@@ -502,11 +513,12 @@ __global__ __launch_bounds__(128) void attn_merge_kernel(MergeArgs a) {
     }
     __syncthreads();
     if (dd >= a.d) return;
-    const float *po = a.ph[0].part_o + dd;
     float num = 0.f;
-    int i = 0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+        if (u < n_items) num += v[u] * s_w[u];
+    int i = 4;
     for (; i + 4 <= n_items; i += 4) {
-        float v[4];
 #pragma unroll
         for (int u = 0; u < 4; ++u) v[u] = po[(size_t)s_row[i + u] * a.d];
 #pragma unroll
