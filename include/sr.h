@@ -393,7 +393,8 @@ int sr_probe_mfma_bf16(void *scratch, size_t scratch_bytes, int iters, void *str
  * One layer's decode attention launch at the 7B attention shape (28 query / 4 kv heads of 128, 64-token pages) on
  * synthetic pages, for studying its phases apart: phases = 1 the shared-prompt phase alone (one unit per group, the
  * members' query rows batched over each prompt block), 2 the private phase alone (one unit per sequence, priv_splits
- * splits of priv_tokens tokens), 3 both in one launch as sr_decode_step runs them.  hot != 0: every page-table entry
+ * splits of priv_tokens tokens), 3 both in one launch as sr_decode_step runs them; adding 4 puts the launch that merges
+ * the partial results behind each attention launch (the duration is then that of the pair).  hot != 0: every page-table entry
  * names one of a few pages, so all K/V loads are cache hits.  Allocates and frees its own buffers, waits for the
  * stream, and writes the mean launch duration in microseconds and the K/V bytes one launch has to read to HOST doubles.
  */

@@ -199,7 +199,8 @@ def sr_probe_hbm(src, dst, mode: int, iters: int = 10, stream=None) -> float:
 
 def sr_probe_decode_attention(n_groups: int, G: int, shared_tokens: int, priv_tokens: int, priv_splits: int,
                               phases: int, hot: bool = False, iters: int = 24, stream=None):
-    """(microseconds per launch, K/V bytes per launch) of one layer's decode attention on synthetic pages."""
+    """(microseconds per launch, K/V bytes per launch) of one layer's decode attention on synthetic pages;
+    phases: 1 shared prompt, 2 private, 3 both in one launch, +4 with the merge launch behind it."""
     us, nbytes = ctypes.c_double(), ctypes.c_double()
     _check(lib().sr_probe_decode_attention(n_groups, G, shared_tokens, priv_tokens, priv_splits, phases, int(hot), iters,
                                            _stream(stream), ctypes.byref(us), ctypes.byref(nbytes)),

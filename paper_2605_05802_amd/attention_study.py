@@ -20,7 +20,7 @@ def main():
     ap.add_argument("--groups", type=int, default=16)
     ap.add_argument("--G", type=int, default=8)
     ap.add_argument("--shared", type=int, default=1024)
-    ap.add_argument("--phases", type=int, default=0, help="1 shared, 2 private, 3 fused; 0 = the whole table")
+    ap.add_argument("--phases", type=int, default=0, help="1 shared, 2 private, 3 fused, 7 fused + merge launch; 0 = the whole table")
     ap.add_argument("--priv", type=int, default=1000)
     ap.add_argument("--splits", type=int, default=2)
     ap.add_argument("--hot", action="store_true")
@@ -39,7 +39,8 @@ def main():
     print("|---|---|---|---|---|---|---|---|")
     for groups in (args.groups, args.groups * 5 // 8):
         for priv, splits in ((100, 1), (500, 2), (1000, 2), (1900, 2 if groups == args.groups else 3)):
-            for ph, name in ((1, "shared prompt"), (2, "private"), (3, "both, one launch")):
+            for ph, name in ((1, "shared prompt"), (2, "private"), (3, "both, one launch"),
+                             (7, "both, and the merge launch")):
                 if ph == 1 and priv != 1000:
                     continue
                 us, nbytes = sr_probe_decode_attention(groups, args.G, args.shared, priv, splits, ph, False)

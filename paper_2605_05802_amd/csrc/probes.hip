@@ -131,7 +131,7 @@ extern "C" int sr_probe_decode_attention(int n_groups, int G, int shared_tokens,
                                          double *host_kv_bytes) {
     const int n_q = 28, n_kv = 4, d = 128, page_tokens = 64, n_rep = n_q / n_kv, NL = 6;   // the 7B attention shape
     if (n_groups < 1 || G < 2 || G > 16 || shared_tokens < 0 || shared_tokens % page_tokens || priv_tokens < 1 ||
-        priv_splits < 1 || priv_splits > 16 || phases < 1 || phases > 3 || iters < 1 || !host_us)
+        priv_splits < 1 || priv_splits > 16 || phases < 1 || phases > 7 || !(phases & 3) || iters < 1 || !host_us)
         return SR_E_ARG;
     if ((phases & 1) && shared_tokens == 0) return SR_E_ARG;
     hipStream_t st = (hipStream_t)stream;
@@ -144,6 +144,8 @@ extern "C" int sr_probe_decode_attention(int n_groups, int G, int shared_tokens,
     uint16_t *kp = nullptr, *vp = nullptr, *q = nullptr;
     int32_t *dpt = nullptr;
     float *po = nullptr, *pml = nullptr;
+    uint4 *merged = nullptr;
+    const int mt_total = ceil_div(M, 16);
     std::vector<int32_t> pt((size_t)M * max_pages);
     for (int u = 0; u < M; ++u)
         for (int j = 0; j < max_pages; ++j) {
@@ -174,6 +176,8 @@ extern "C" int sr_probe_decode_attention(int n_groups, int G, int shared_tokens,
     if (rc == SR_OK && (e = hipMalloc(&dpt, pt.size() * 4)) != hipSuccess) fail(e, "hipMalloc");
     if (rc == SR_OK && (e = hipMalloc(&po, (items0 + items1) * 16 * d * 4)) != hipSuccess) fail(e, "hipMalloc");
     if (rc == SR_OK && (e = hipMalloc(&pml, (items0 + items1) * 16 * 2 * 4)) != hipSuccess) fail(e, "hipMalloc");
+    if (rc == SR_OK && (phases & 4) && (e = hipMalloc(&merged, (size_t)mt_total * 16 * n_q * d * 2)) != hipSuccess)
+        fail(e, "hipMalloc");
     if (rc == SR_OK) {
         (void)hipMemsetAsync(kp, 0x11, layer_elems * 2 * NL, st);      // small finite bf16 values
         (void)hipMemsetAsync(vp, 0x11, layer_elems * 2 * NL, st);
@@ -187,8 +191,8 @@ extern "C" int sr_probe_decode_attention(int n_groups, int G, int shared_tokens,
         a.q = q; a.page_table = dpt; a.pt_stride = max_pages; a.page_tokens = page_tokens;
         a.n_q = n_q; a.n_kv = n_kv; a.d = d; a.scale = 0.0883883f;
         AttnPhase ph[2] = {x, y};
-        const AttnPhase *first = phases == 2 ? ph + 1 : ph;
-        const int n_ph = phases == 3 ? 2 : 1;
+        const AttnPhase *first = (phases & 3) == 2 ? ph + 1 : ph;
+        const int n_ph = (phases & 3) == 3 ? 2 : 1;
         int layer = 0;
         double ms = 0;
         int lrc = SR_OK;
@@ -196,7 +200,8 @@ extern "C" int sr_probe_decode_attention(int n_groups, int G, int shared_tokens,
             a.kpool = kp + (size_t)(layer % NL) * layer_elems;
             a.vpool = vp + (size_t)(layer % NL) * layer_elems;
             ++layer;
-            const int r = launch_attention(a, first, n_ph, st);
+            int r = launch_attention(a, first, n_ph, st);
+            if (r == SR_OK && (phases & 4)) r = launch_attn_merge(a, first, n_ph, M, merged, mt_total, nullptr, st);
             if (r != SR_OK) lrc = r;
         });
         if (rc == SR_OK) rc = lrc;
@@ -212,5 +217,6 @@ extern "C" int sr_probe_decode_attention(int n_groups, int G, int shared_tokens,
     if (dpt) (void)hipFree(dpt);
     if (po) (void)hipFree(po);
     if (pml) (void)hipFree(pml);
+    if (merged) (void)hipFree(merged);
     return rc;
 }
