@@ -390,6 +390,20 @@ int sr_probe_hbm(const void *src, void *dst, size_t bytes, int mode, int iters, 
 int sr_probe_mfma_bf16(void *scratch, size_t scratch_bytes, int iters, void *stream, double *host_TFLOPs);
 
 /*
+ * The matrix-core loop with operand-sized loads beside it, for telling what the operand traffic of a tiled GEMM leaves
+ * of the matrix pipe: 256 workgroups of eight wavefronts; every wavefront alternates sixteen register-resident
+ * 32x32x16 bf16 MFMAs with loads_per_16 (2, 4 or 8; 0 with path 0) wavefront-wide loads of 16 bytes per lane from buf,
+ * into registers (path 1) or straight into LDS (path 2); lds_reads != 0 adds twelve 16-byte LDS reads per sixteen MFMAs
+ * (paths 0 and 2).  A 256 x 256 x 32 GEMM step on eight computing wavefronts corresponds to loads_per_16 = 4.
+ * buf: device memory, buf_bytes a power of two >= 64 KiB (small = L2 resident; read only).  scratch: device memory of
+ * at least 512 KiB that receives one float per thread.  Waits for the stream; writes the matrix rate and the rate of
+ * the loads to HOST doubles (host_load_GBs may be null).  SR_E_ARG for any other combination.
+ */
+int sr_probe_mfma_under_loads(const void *buf, size_t buf_bytes, void *scratch, size_t scratch_bytes, int path,
+                              int loads_per_16, int lds_reads, int iters, void *stream, double *host_TFLOPs,
+                              double *host_load_GBs);
+
+/*
  * One layer's decode attention launch at the 7B attention shape (28 query / 4 kv heads of 128, 64-token pages) on
  * synthetic pages, for studying its phases apart: phases = 1 the shared-prompt phase alone (one unit per group, the
  * members' query rows batched over each prompt block), 2 the private phase alone (one unit per sequence, priv_splits

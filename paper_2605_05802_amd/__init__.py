@@ -20,7 +20,7 @@ EXPORTS = ("sr_init", "sr_destroy", "sr_load_weights", "sr_prefill_chunk", "sr_d
            "sr_retire_and_compact", "sr_gate_batch", "sr_set_actions", "sr_get_actions", "sr_get_logits",
            "sr_get_live_map", "sr_stats", "sr_strerror", "sr_profile", "sr_profile_read", "sr_signals_batch",
            "sr_score_chunk", "sr_get_logprob", "sr_grpo_loss", "sr_finish_sequences", "sr_grpo_loss_static",
-           "sr_probe_hbm", "sr_probe_mfma_bf16", "sr_gate_batch_antidiag",
+           "sr_probe_hbm", "sr_probe_mfma_bf16", "sr_probe_mfma_under_loads", "sr_gate_batch_antidiag",
            "sr_probe_decode_attention")
 
 KERNEL_CLASSES = ("norm", "gemm_qkv", "qkv_post", "attn_decode", "attn_prefill", "attn_merge",
@@ -100,6 +100,8 @@ def lib():
         L.sr_probe_decode_attention.argtypes = [ci] * 8 + [vp, ctypes.POINTER(ctypes.c_double),
                                                   ctypes.POINTER(ctypes.c_double)]
         L.sr_probe_mfma_bf16.argtypes = [vp, ctypes.c_size_t, ci, vp, ctypes.POINTER(ctypes.c_double)]
+        L.sr_probe_mfma_under_loads.argtypes = [vp, ctypes.c_size_t, vp, ctypes.c_size_t, ci, ci, ci, ci, vp,
+                                                ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_double)]
         L.sr_finish_sequences.argtypes = [vp, vp, ctypes.POINTER(ci), vp]
         L.sr_set_actions.argtypes = [vp, ci, vp, vp]
         L.sr_get_actions.argtypes = [vp, vp, vp]
@@ -214,6 +216,17 @@ def sr_probe_mfma_bf16(scratch, iters: int = 3, stream=None) -> float:
     _check(lib().sr_probe_mfma_bf16(_ptr(scratch), scratch.numel() * scratch.element_size(), iters, _stream(stream),
                                     ctypes.byref(out)), "sr_probe_mfma_bf16")
     return out.value
+
+
+def sr_probe_mfma_under_loads(buf, scratch, path: int, loads_per_16: int, lds_reads: bool = False, iters: int = 3,
+                              stream=None):
+    """(TFLOP/s of the matrix loop, GB/s of the loads beside it); path 0 none, 1 into registers, 2 straight into LDS."""
+    tf, gb = ctypes.c_double(), ctypes.c_double()
+    _check(lib().sr_probe_mfma_under_loads(_ptr(buf), buf.numel() * buf.element_size(), _ptr(scratch),
+                                           scratch.numel() * scratch.element_size(), path, loads_per_16, int(lds_reads),
+                                           iters, _stream(stream), ctypes.byref(tf), ctypes.byref(gb)),
+           "sr_probe_mfma_under_loads")
+    return tf.value, gb.value
 
 
 class Context:

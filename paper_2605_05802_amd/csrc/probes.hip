@@ -61,6 +61,64 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(float *out, int iters) 
     out[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
 }
 
+// The matrix-core loop with operand-sized loads beside it: every wavefront alternates sixteen register-resident
+// 32x32x16 MFMAs with L wavefront-wide loads of 16 bytes per lane from a small buffer (a power of two of 16-byte
+// vectors, so L2- or memory-side-cache resident), either into registers (PATH 1) or straight into LDS (PATH 2), and
+// optionally twelve 16-byte LDS reads.  A 256 x 256 x 32 GEMM step with eight computing wavefronts is L = 4.
+template <int PATH, int L, bool DS>
+__global__ __launch_bounds__(512) void probe_mfma_loads_kernel(const u32x4 *__restrict__ src, size_t vec_mask, float *out,
+                                                               int iters) {
+    __shared__ u32x4 lds[8 * 8 * 64];     // 64 KiB: eight 1 KiB landing slots per wavefront
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    f32x16 acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+    bf16x8 a, b;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { a[e] = (__bf16)(0.001f * (lane + e)); b[e] = (__bf16)(0.002f * (lane - e)); }
+    u32x4 sink = {0, 0, 0, 0};
+    size_t pos = ((size_t)blockIdx.x * 8 + wave) * 4096 + lane;
+    constexpr int NL = L > 0 ? L : 1;
+    u32x4 r[2][NL];                        // the loads of one iteration are consumed two iterations later
+#pragma unroll
+    for (int p = 0; p < 2; ++p)
+#pragma unroll
+        for (int j = 0; j < NL; ++j) r[p][j] = sink;
+    for (int it = 0; it < iters; ++it) {
+        const int p = it & 1;
+        if constexpr (PATH == 1) {
+#pragma unroll
+            for (int j = 0; j < L; ++j) { sink ^= r[p][j]; r[p][j] = src[(pos + j * 64) & vec_mask]; }
+        } else if constexpr (PATH == 2) {
+#pragma unroll
+            for (int j = 0; j < L; ++j)
+                __builtin_amdgcn_global_load_lds(
+                    (const __attribute__((address_space(1))) void *)(src + ((pos + j * 64 - lane) & vec_mask) + lane),
+                    (__attribute__((address_space(3))) void *)&lds[(wave * 8 + (j & 7)) * 64], 16, 0, 0);
+        }
+        if constexpr (DS) {
+#pragma unroll
+            for (int j = 0; j < 12; ++j) sink ^= lds[((wave * 8 + (j & 7)) * 64 + lane + it) & (8 * 8 * 64 - 1)];
+        }
+        pos += (size_t)L * 64;
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[i], 0, 0, 0);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);    // every load has landed before the wavefront (and its LDS) goes away
+#pragma unroll
+    for (int p = 0; p < 2; ++p)
+#pragma unroll
+        for (int j = 0; j < NL; ++j) sink ^= r[p][j];
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) t += acc[i][0];
+    out[(size_t)blockIdx.x * 512 + threadIdx.x] = t + (float)((sink.x ^ sink.y ^ sink.z ^ sink.w) & 1u);
+}
+
 int time_launches(hipStream_t st, int iters, double *ms_per_launch, const std::function<void()> &launch) {
     hipEvent_t e0, e1;
     SR_HIP(hipEventCreate(&e0));
@@ -119,6 +177,45 @@ extern "C" int sr_probe_mfma_bf16(void *scratch, size_t scratch_bytes, int iters
                          [&] { probe_mfma_kernel<<<dim3(wgs), dim3(256), 0, st>>>((float *)scratch, inner); }));
     const double flop = (double)wgs * 4 * inner * 4 * 2.0 * 32 * 32 * 16;
     *host_TFLOPs = flop / (ms * 1e-3) / 1e12;
+    return SR_OK;
+}
+
+#define SR_PROBE_CASE(P, LL, D)                                                                                  \
+    case P * 100 + LL * 2 + D:                                                                                   \
+        probe_mfma_loads_kernel<P, LL, D != 0><<<dim3(wgs), dim3(512), 0, st>>>(src, mask, out, inner);          \
+        break;
+
+extern "C" int sr_probe_mfma_under_loads(const void *buf, size_t buf_bytes, void *scratch, size_t scratch_bytes, int path,
+                                         int loads_per_16, int lds_reads, int iters, void *stream, double *host_TFLOPs,
+                                         double *host_load_GBs) {
+    const int wgs = 256;                           // one workgroup of eight wavefronts per compute unit
+    if (!buf || !scratch || !host_TFLOPs || iters < 1 || path < 0 || path > 2 || scratch_bytes < (size_t)wgs * 512 * 4)
+        return SR_E_ARG;
+    if (buf_bytes < (1u << 16) || (buf_bytes & (buf_bytes - 1))) return SR_E_ARG;      // a power of two, >= 64 KiB
+    if (path == 0 ? loads_per_16 != 0 : (loads_per_16 != 2 && loads_per_16 != 4 && loads_per_16 != 8)) return SR_E_ARG;
+    if (lds_reads && path == 1) return SR_E_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    const u32x4 *src = (const u32x4 *)buf;
+    const size_t mask = buf_bytes / 16 - 1;
+    float *out = (float *)scratch;
+    const int inner = 4000;
+    const int key = path * 100 + loads_per_16 * 2 + (lds_reads ? 1 : 0);
+    double ms = 0;
+    int bad = 0;
+    auto launch = [&] {
+        switch (key) {
+            SR_PROBE_CASE(0, 0, 0) SR_PROBE_CASE(0, 0, 1)
+            SR_PROBE_CASE(1, 2, 0) SR_PROBE_CASE(1, 4, 0) SR_PROBE_CASE(1, 8, 0)
+            SR_PROBE_CASE(2, 2, 0) SR_PROBE_CASE(2, 4, 0) SR_PROBE_CASE(2, 8, 0)
+            SR_PROBE_CASE(2, 2, 1) SR_PROBE_CASE(2, 4, 1) SR_PROBE_CASE(2, 8, 1)
+            default: bad = 1;
+        }
+    };
+    SR_TRY(time_launches(st, iters, &ms, launch));
+    if (bad) return SR_E_ARG;
+    const double flop = (double)wgs * 8 * inner * 16 * 2.0 * 32 * 32 * 16;
+    *host_TFLOPs = flop / (ms * 1e-3) / 1e12;
+    if (host_load_GBs) *host_load_GBs = (double)wgs * 8 * inner * loads_per_16 * 1024.0 / (ms * 1e-3) / 1e9;
     return SR_OK;
 }
 
