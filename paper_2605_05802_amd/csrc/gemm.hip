@@ -349,6 +349,186 @@ __global__ __launch_bounds__(kPfThreads) void gemm_prefill_kernel(GemmArgs a, in
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Batches of a few hundred rows (decode steps of a 512-sequence batch) against a wide matrix: neither a weight
+// stream (the matrix pipe, not HBM, bounds 512 rows) nor a large tiled GEMM (two row blocks of 256 leave 1.16 rounds
+// of tiles and fetch every weight from HBM with only two workgroups sharing it).  One workgroup takes ALL rows (up
+// to 512) of 160 packed features, so every weight byte is fetched from HBM exactly once and the 37 888 packed
+// gate|up rows of the 7B shape break into 237 workgroups, one round.  Eight wavefronts, each 64 rows x 160 features
+// (2 x 5 accumulator tiles of 32 x 32 = 160 registers; seven LDS fragment reads per ten MFMAs).  Both operands go
+// global -> LDS with direct-to-LDS loads, one barrier per k-step: X (32 KiB per k-step, L2 resident) two k-steps
+// ahead through three buffers, W (10 KiB per k-step, from HBM) five k-steps ahead through six;
+// each wavefront copies the X rows it consumes itself and its share of the ten W tiles.  The copies are issued
+// from inline assembly: the compiler's wait-count pass then neither sees them nor waits for them before the LDS
+// reads, and the wait for the stage that is needed is placed by hand (vector-memory operations of a wavefront
+// retire in order, so "all but the newer stage's copies" is a count).
+// ---------------------------------------------------------------------------------------------
+constexpr int kMidThreads = 512;
+constexpr int kMidWTiles = 10;                                     // 160 packed features
+constexpr int kMidXTiles = 32;                                     // 512 rows
+constexpr int kMidXBufs = 3, kMidWBufs = 6;                        // k-steps of X (from L2) and of W (from HBM) in LDS
+constexpr int kMidXVec = kMidXTiles * 64, kMidWVec = kMidWTiles * 64;       // u32x4 per k-step: 32 KiB and 10 KiB
+constexpr int kMidLdsBytes = (kMidXBufs * kMidXVec + kMidWBufs * kMidWVec) * 16;   // 156 KiB
+
+__device__ __forceinline__ void lds_dma16(const u32x4 *g, unsigned lds_byte_offset) {
+    asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(lds_byte_offset) : "memory");
+}
+
+// wait until at most n of this wavefront's vector-memory operations are outstanding (n uniform, 0..8)
+__device__ __forceinline__ void wait_vm_at_most(int n) {
+    switch (n) {
+        case 0: __builtin_amdgcn_s_waitcnt(0x0F70); break;
+        case 1: __builtin_amdgcn_s_waitcnt(0x0F71); break;
+        case 2: __builtin_amdgcn_s_waitcnt(0x0F72); break;
+        case 3: __builtin_amdgcn_s_waitcnt(0x0F73); break;
+        case 4: __builtin_amdgcn_s_waitcnt(0x0F74); break;
+        case 5: __builtin_amdgcn_s_waitcnt(0x0F75); break;
+        case 6: __builtin_amdgcn_s_waitcnt(0x0F76); break;
+        case 7: __builtin_amdgcn_s_waitcnt(0x0F77); break;
+        default: __builtin_amdgcn_s_waitcnt(0x0F78); break;
+    }
+}
+
+template <int EPI>
+__global__ __launch_bounds__(kMidThreads) void gemm_mid_kernel(GemmArgs a) {
+    extern __shared__ u32x4 mid_lds[];      // X ring [kMidXBufs][32 tiles x 64], then W ring [kMidWBufs][10 tiles x 64]
+
+    const int nb = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const bool active = wave * 64 < a.M;               // this wavefront's 64 rows hold valid rows
+    const int n_stages = a.ks_total;
+
+    // copies of one k-step: this wavefront's four X tiles (if it has rows) and W tiles wave, wave + 8
+    const int n_w = wave + 8 < kMidWTiles ? 2 : 1;
+    const u32x4 *xsrc = (const u32x4 *)a.X + (size_t)(wave * 4) * 64 + lane;                       // + ks * mt_total * 64
+    const u32x4 *wsrc = (const u32x4 *)a.W + ((size_t)(nb * kMidWTiles + wave) * a.ks_total) * 64 + lane;   // + ks * 64
+    const unsigned lds_x = (unsigned)(size_t)(__attribute__((address_space(3))) void *)mid_lds;
+    const unsigned lds_w = lds_x + (unsigned)(kMidXBufs * kMidXVec) * 16;
+    auto copy_x = [&](int st) {             // past the end: a harmless re-read of the last k-step, never consumed
+        if (!active) return;
+        const int ks = min(st, n_stages - 1);
+        const unsigned base = lds_x + (unsigned)((st % kMidXBufs) * kMidXVec + wave * 4 * 64) * 16;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) lds_dma16(xsrc + ((size_t)ks * a.mt_total + t) * 64, base + (unsigned)(t * 64) * 16);
+    };
+    auto copy_w = [&](int st) {
+        const int ks = min(st, n_stages - 1);
+        const unsigned base = lds_w + (unsigned)((st % kMidWBufs) * kMidWVec + wave * 64) * 16;
+        lds_dma16(wsrc + (size_t)ks * 64, base);
+        if (n_w == 2) lds_dma16(wsrc + ((size_t)8 * a.ks_total + ks) * 64, base + (unsigned)(8 * 64) * 16);
+    };
+
+    f32x16 acc[5][2];                        // [feature group of 32][row group of 32]
+#pragma unroll
+    for (int i = 0; i < 5; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    const int r32 = lane & 31, g2 = lane >> 5;
+    const int sub = r32 >> 4, slot0 = (r32 & 15) + 16 * g2;
+    const int woff = kMidXBufs * kMidXVec + sub * 64 + slot0;              // + W buffer + i * 128 + h * 32
+    const int xoff = (wave * 4 + sub) * 64 + slot0;                        // + X buffer + j * 128 + h * 32
+
+    // Vector-memory operations of a wavefront retire in order.  Every iteration issues X of k-step s + 2, then W of
+    // k-step s + 5; the prologue issues the same pattern for the two iterations before the first, behind W 0..2.
+    // So when iteration s begins, what was issued after X(s) is W(s+3), X(s+1), W(s+4), and W(s) is older than X(s).
+    copy_w(0); copy_w(1); copy_w(2);
+    copy_x(0); copy_w(3);
+    copy_x(1); copy_w(4);
+    const int n_newer = (active ? 4 : 0) + 2 * n_w;
+    int bx = 0, bw = 0;
+    for (int s = 0; s < n_stages; ++s) {
+        wait_vm_at_most(n_newer);            // X(s) and W(s) have landed
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();        // ... for every wavefront, and nobody reads k-step s - 1 any more
+        asm volatile("" ::: "memory");
+        copy_x(s + 2);                       // into the buffers k-step s - 1 used
+        copy_w(s + 5);
+        const u32x4 *xb = mid_lds + bx * kMidXVec, *wb = mid_lds + bw * kMidWVec;
+        bx = bx == kMidXBufs - 1 ? 0 : bx + 1;
+        bw = bw == kMidWBufs - 1 ? 0 : bw + 1;
+        if (active) {
+            bf16x8 wf[2][5], xf[2][2];       // [k-half parity][group]
+#pragma unroll
+            for (int i = 0; i < 5; ++i) wf[0][i] = __builtin_bit_cast(bf16x8, wb[woff + i * 128]);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) xf[0][j] = __builtin_bit_cast(bf16x8, xb[xoff + j * 128]);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < 5; ++i) wf[1][i] = __builtin_bit_cast(bf16x8, wb[woff + i * 128 + 32]);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) xf[1][j] = __builtin_bit_cast(bf16x8, xb[xoff + j * 128 + 32]);
+#pragma unroll
+            for (int i = 0; i < 5; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[0][i], xf[0][j], acc[i][j], 0, 0, 0);
+#pragma unroll
+            for (int f = 0; f < 7; ++f) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 LDS read
+            }
+            __builtin_amdgcn_sched_group_barrier(0x008, 3, 0);
+#pragma unroll
+            for (int i = 0; i < 5; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[1][i], xf[1][j], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);      // the copies past the end have landed before LDS goes away
+    if (!active) return;
+
+    // accumulator (i, j): lane (r32 = row within the 32-row group, g2) holds, in register v,
+    // feature 8 * (v / 4) + 4 * g2 + v % 4 of the 32-feature group
+    if constexpr (EPI == EPI_F32) {
+        float *out = (float *)a.out;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int m = wave * 64 + j * 32 + r32;
+            if (m < a.M) {
+#pragma unroll
+                for (int i = 0; i < 5; ++i)
+#pragma unroll
+                    for (int vq = 0; vq < 4; ++vq) {
+                        const int n = nb * 160 + i * 32 + 8 * vq + 4 * g2;
+                        if (n < a.N)
+                            *(f32x4 *)(out + (size_t)m * a.ld_out + n) =
+                                f32x4{acc[i][j][4 * vq], acc[i][j][4 * vq + 1], acc[i][j][4 * vq + 2], acc[i][j][4 * vq + 3]};
+                    }
+            }
+        }
+    } else {
+        uint16_t *out = (uint16_t *)a.out;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int m = wave * 64 + j * 32 + r32;
+            if (m < a.M) {
+#pragma unroll
+                for (int i = 0; i < 5; ++i)
+#pragma unroll
+                    for (int vq = 0; vq < 2; ++vq) {
+                        const int f = nb * 80 + i * 16 + 8 * vq + 4 * g2;
+                        if (f < a.ld_out) {
+                            float r[4];
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const float gt = acc[i][j][4 * vq + e];
+                                r[e] = gt / (1.0f + __expf(-gt)) * acc[i][j][4 * (vq + 2) + e];
+                            }
+                            uint2 v = make_uint2(pack_bf16x2(r[0], r[1]), pack_bf16x2(r[2], r[3]));
+                            *(uint2 *)(out + frag_offset(m, f, a.mt_total)) = v;
+                        }
+                    }
+            }
+        }
+    }
+}
+
 // One thread per 16-byte lane slot of the packed matrix.
 __global__ void pack_rows_kernel(const uint16_t *__restrict__ src, int n_rows, int K, uint16_t *__restrict__ dst,
                                  int ks_total, int dst_row0, int interleave16, int which) {
@@ -418,6 +598,25 @@ int launch_tiles128(const GemmArgs &a, GemmEpilogue epi, hipStream_t stream) {
     return SR_OK;
 }
 
+// All rows (at most 512) of 160 packed features per workgroup; no K split.  The last workgroup reads whole tiles
+// past N: the packed matrix is allocated (and zero) up to a multiple of 160 rows.
+int launch_mid(const GemmArgs &a, GemmEpilogue epi, hipStream_t stream) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        SR_HIP(hipFuncSetAttribute((const void *)gemm_mid_kernel<EPI_F32>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   kMidLdsBytes));
+        SR_HIP(hipFuncSetAttribute((const void *)gemm_mid_kernel<EPI_SWIGLU>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   kMidLdsBytes));
+        attr_set = true;
+    }
+    if (a.M > 512 || a.splits != 1 || a.ks_total < 1 || round_up(a.M, 64) > a.mt_total * 16) return SR_E_ARG;
+    dim3 grid((unsigned)ceil_div(a.N, 160)), block(kMidThreads);
+    if (epi == EPI_F32) gemm_mid_kernel<EPI_F32><<<grid, block, kMidLdsBytes, stream>>>(a);
+    else gemm_mid_kernel<EPI_SWIGLU><<<grid, block, kMidLdsBytes, stream>>>(a);
+    SR_HIP(hipGetLastError());
+    return SR_OK;
+}
+
 // `a` restricted to the packed columns from c0 (a multiple of 256) on
 GemmArgs columns_from(const GemmArgs &a, GemmEpilogue epi, int c0) {
     GemmArgs b = a;
@@ -450,6 +649,8 @@ int launch_gemm(const GemmArgs &a, GemmEpilogue epi, hipStream_t stream) {
             if (a.N >= 16384 || (a.N >= 2048 && fills)) return launch_tiles256(a, epi, stream);
             return launch_tiles128(a, epi, stream);
         }
+        // A few hundred rows against a wide matrix (gate|up, LM head): every row in one workgroup of 160 features
+        if (a.M <= 512 && a.N >= 16384) return launch_mid(a, epi, stream);
         // A few hundred rows (decode steps of a large batch).  256 x 256 tiles run one workgroup per CU in whole
         // rounds of 256; 128 x 128 tiles run two per CU and drain almost continuously.  Measured at 304 and 512
         // rows, K = 3584: 150 us a round (the weights come from HBM: only two row blocks share them) against 0.166 us

@@ -341,8 +341,8 @@ def test_long_shared_prompt_in_several_passes():
 
 def test_mid_size_batch_takes_mixed_tiles_and_split_k():
     """512 rows per decode step, 304 after the gate (the shape of the 64-group configuration): between 129 and
-    1024 rows the wide gate|up projection (here 33 792 packed columns) runs whole rounds of 256 x 256 tiles over
-    its first columns and 128 x 128 tiles over the rest, and the thin projections are split along K; every logit
+    512 rows the wide gate|up projection (here 33 792 packed columns) runs on the kernel that gives all rows of 160
+    packed columns to one workgroup, and the thin projections are split along K on the tiled kernels; every logit
     of every row is compared with the checker."""
     shape = synth.ModelShape(1, 256, 4, 2, 64, 16896, 1024)
     cfg = synth.EpisodeConfig("mid", 64, 8, 16, 2, 2, 2, 64, (1,), 0.3, 0.4)
@@ -356,7 +356,7 @@ def test_mid_size_batch_takes_mixed_tiles_and_split_k():
 def test_mid_size_batch_at_the_full_hidden_size():
     """The same regime at the inner dimension of the 7B shape (hidden 3584, 28 query / 4 kv heads of 128, one layer):
     384 rows per decode step, fewer after the gate, so the QKV, O and down projections run split along K = 3584 /
-    16896 on the tiled kernels and the gate|up projection on whole rounds of large tiles plus small ones; every logit
+    16896 on the tiled kernels and the gate|up projection on the all-rows-per-workgroup kernel; every logit
     of every row against the checker, bound by the general rule (the contract mode on six sequences)."""
     shape = synth.ModelShape(1, 3584, 28, 4, 128, 16896, 1024)
     cfg = synth.EpisodeConfig("mid-3584", 48, 8, 8, 2, 2, 2, 64, (1,), 0.3, 0.4)
@@ -368,6 +368,20 @@ def test_mid_size_batch_at_the_full_hidden_size():
           f"mismatches = {mism}, near ties = {near}, rows after the gate = {stats['n_live_seq']}")
     assert 128 < stats["n_live_seq"] < 384
     assert worst <= tol and all(g < gap_rule(tol) for g in info["mismatch_gaps"])
+
+
+def test_mid_size_batch_with_ragged_wide_matrices():
+    """296 rows per decode step (four 64-row slabs and one of 40 rows), fewer after the gate, against a gate|up
+    matrix of 16 416 packed columns and an LM head of 16 400 rows, neither a multiple of the 160 columns a workgroup
+    of the all-rows kernel takes: both of its epilogues (SwiGLU to bf16, fp32 logits), its ragged last workgroup and
+    its ragged last row slab, every logit of every row against the checker."""
+    shape = synth.ModelShape(1, 256, 4, 2, 64, 8208, 16400)
+    cfg = synth.EpisodeConfig("mid-ragged", 37, 8, 8, 2, 2, 2, 64, (1,), 0.3, 0.4)
+    rec, stats, worst, mism, near = run_and_compare(shape, cfg, seed=21, page_tokens=32, kv_pool_bytes=1 << 28)
+    print(f"mid, ragged: worst |dlogit| = {worst:.3e}, mismatches = {mism}, near ties = {near}, "
+          f"rows after the gate = {stats['n_live_seq']}")
+    assert 128 < stats["n_live_seq"] < 296
+    assert worst <= LOGIT_TOL and mism == 0
 
 
 def test_7b_shape_sampled_sequences():
