@@ -205,7 +205,7 @@ int timed(sr_ctx *c, int kc, hipStream_t st, F &&launch) {
 // wavefront; the number of computing wavefronts per workgroup (32 features each) is picked so that
 // the matrix breaks into about 256 workgroups with as few K splits as possible: the packed gate|up
 // matrix (37 888 rows at the 7B shape) gives 237 workgroups of 160 features, the down projection
-// 28 blocks of 128 features x 9 splits, the LM head 256-feature workgroups over several rounds.
+// 28 blocks of 128 features x 9 splits, the LM head 320-feature workgroups over two rounds.
 // Thin ones keep the 4-wavefront kernel and are split along K so that about one workgroup per CU is
 // in flight -- more than that only adds partial-sum traffic.  Batches of 129 .. 1024 rows split thin matrices a
 // little (pick_splits); larger ones (prefill) never split.
@@ -216,7 +216,11 @@ int decode_waves(int M, int N, int ks_total, bool swiglu) {
     // K splits instead of seven -- the projection itself takes the same time (13.9 against 13.0 us, 11.4 against
     // 11.8 us at the 7B shape) and the kernel that adds the partial sums reads half as many
     if (N < 8192 && ks_total < 256) return 2;
-    return N >= 8192 ? 8 : 4;
+    if (N < 8192) return 4;
+    // wide and shallow (the LM head): 256- or 320-feature workgroups, whichever leaves fewer workgroup-rounds of work
+    // on 256 CUs (152 064 rows: 594 workgroups = 3 rounds of 8 wavefronts, or 476 = 2 rounds of 10; 226 against 246 us)
+    const int r8 = ceil_div(ceil_div(N, 256), 256) * 8, r10 = ceil_div(ceil_div(N, 320), 256) * 10;
+    return r10 < r8 ? 10 : 8;
 }
 
 int pick_splits(int M, int N, int ks_total) {
@@ -246,8 +250,10 @@ int pick_splits(int M, int N, int ks_total) {
 int alloc_packed(sr_ctx *c, PackedMat *m, int n_rows, int K, hipStream_t st) {
     m->N = n_rows;
     m->ks = round_up(ceil_div(K, 32), 16);       // the GEMMs consume k-steps in groups of 16
-    // row padding covers both workgroup widths of the decode kernels (256 and 160 features)
-    const int rows = round_up(n_rows, 256) > round_up(n_rows, 160) ? round_up(n_rows, 256) : round_up(n_rows, 160);
+    // row padding covers every workgroup width of the decode kernels (256, 160 and 320 features)
+    int rows = round_up(n_rows, 256);
+    if (round_up(n_rows, 160) > rows) rows = round_up(n_rows, 160);
+    if (round_up(n_rows, 320) > rows) rows = round_up(n_rows, 320);
     const size_t elems = (size_t)rows * m->ks * 32;
     SR_TRY(dev_alloc(c, &m->p, elems));
     SR_HIP(hipMemsetAsync(m->p, 0, elems * 2, st));

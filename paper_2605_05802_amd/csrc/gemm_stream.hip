@@ -219,7 +219,7 @@ int launch_gemm_stream(const GemmArgs &a, GemmEpilogue epi, hipStream_t stream) 
     if (a.M <= 0) return SR_OK;
     if (a.M > 128 || a.mt_total < 8 || a.splits < 1 || a.splits > 65535) return SR_E_ARG;
     const int ring = a.ring == 16 ? 16 : 8;
-    if (a.ks_total % ring || (a.wide != 2 && a.wide != 4 && a.wide != 5 && a.wide != 8)) return SR_E_ARG;
+    if (a.ks_total % ring || (a.wide != 2 && a.wide != 4 && a.wide != 5 && a.wide != 8 && a.wide != 10)) return SR_E_ARG;
     dim3 sgrid(ceil_div(a.N, 32 * a.wide), 1, epi == EPI_F32 ? a.splits : 1), lblock(64 * (a.wide + 1));
     const int mt32 = ceil_div(a.M, 32);
     hipError_t attr = hipSuccess;
@@ -232,11 +232,11 @@ int launch_gemm_stream(const GemmArgs &a, GemmEpilogue epi, hipStream_t stream) 
      : mt32 == 3 ? SR_STREAM_CASE(E, W, 3, R) : SR_STREAM_CASE(E, W, 4, R))
 #define SR_STREAM_W(E, R)                                                                                   \
     (a.wide == 2 ? SR_STREAM_MT(E, 2, R) : a.wide == 4 ? SR_STREAM_MT(E, 4, R)                               \
-     : a.wide == 5 ? SR_STREAM_MT(E, 5, R) : SR_STREAM_MT(E, 8, R))
+     : a.wide == 5 ? SR_STREAM_MT(E, 5, R) : a.wide == 8 ? SR_STREAM_MT(E, 8, R) : SR_STREAM_MT(E, 10, R))
     // nine wavefronts put three on one SIMD, which leaves too few registers for the deep ring
 #define SR_STREAM_W16(E)                                                                                    \
     (a.wide == 2 ? SR_STREAM_MT(E, 2, 16) : a.wide == 4 ? SR_STREAM_MT(E, 4, 16) : SR_STREAM_MT(E, 5, 16))
-    if (ring == 16 && a.wide == 8) return SR_E_ARG;
+    if (ring == 16 && a.wide >= 8) return SR_E_ARG;
     if (epi == EPI_F32) { if (ring == 16) SR_STREAM_W16(EPI_F32); else SR_STREAM_W(EPI_F32, 8); }
     else { if (ring == 16) SR_STREAM_W16(EPI_SWIGLU); else SR_STREAM_W(EPI_SWIGLU, 8); }
     SR_HIP(attr);

@@ -122,7 +122,7 @@ struct GemmArgs {
     int mt_total;        // row tiles in X (and in a fragment-major output)
     int ks_total;        // k-steps (K padded to 32) in X and W
     int splits;          // split-K factor (EPI_F32 only)
-    int wide;            // M <= 128 only: 2, 4, 5 or 8 = computing wavefronts per workgroup (32 features each) of the
+    int wide;            // M <= 128 only: 2, 4, 5, 8 or 10 = computing wavefronts per workgroup (32 features each) of the
                          // kernel with a loader wavefront; 0 = the 4-wavefront, 128-feature kernel
     int ring;            // with `wide`: k-steps of weights in flight per wavefront, 8 (default) or 16
     void *out;
