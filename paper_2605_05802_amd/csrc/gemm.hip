@@ -529,6 +529,122 @@ __global__ __launch_bounds__(kMidThreads) void gemm_mid_kernel(GemmArgs a) {
     }
 }
 
+// The same kernel for 257 .. 384 rows on 16x16x32 MFMAs: with 64-row slabs five (or six) of the eight wavefronts
+// would have rows, two of them on one SIMD, and that SIMD would carry 128 rows.  Here the 16-row tiles are dealt
+// out round robin, wavefront w owning tiles w, w + 8, w + 16 (at most three), so 19 tiles (304 rows) put 5, 5, 5
+// and 4 on the four SIMDs.  A 16-row fragment-major tile is one MFMA operand as it lies in LDS (one 16-byte read per
+// lane): 10 W + up to 3 X reads for up to 30 MFMAs per k-step.  Copies, rings, barrier and wait counts as above.
+template <int EPI>
+__global__ __launch_bounds__(kMidThreads) void gemm_mid16_kernel(GemmArgs a) {
+    constexpr int RT = 3;
+    extern __shared__ u32x4 mid_lds[];
+
+    const int nb = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n_tiles = (a.M + 15) >> 4;
+    const int my_tiles = wave < n_tiles ? min(RT, (n_tiles - wave + 7) >> 3) : 0;     // tiles wave, wave + 8, ...
+    const int n_stages = a.ks_total;
+
+    const int n_w = wave + 8 < kMidWTiles ? 2 : 1;
+    const u32x4 *xsrc = (const u32x4 *)a.X + (size_t)wave * 64 + lane;                             // + (ks * mt_total + 8 t) * 64
+    const u32x4 *wsrc = (const u32x4 *)a.W + ((size_t)(nb * kMidWTiles + wave) * a.ks_total) * 64 + lane;
+    const unsigned lds_x = (unsigned)(size_t)(__attribute__((address_space(3))) void *)mid_lds;
+    const unsigned lds_w = lds_x + (unsigned)(kMidXBufs * kMidXVec) * 16;
+    auto copy_x = [&](int st) {
+        const int ks = min(st, n_stages - 1);
+        const unsigned base = lds_x + (unsigned)((st % kMidXBufs) * kMidXVec + wave * 64) * 16;
+#pragma unroll
+        for (int t = 0; t < RT; ++t)
+            if (t < my_tiles) lds_dma16(xsrc + ((size_t)ks * a.mt_total + 8 * t) * 64, base + (unsigned)(8 * t * 64) * 16);
+    };
+    auto copy_w = [&](int st) {
+        const int ks = min(st, n_stages - 1);
+        const unsigned base = lds_w + (unsigned)((st % kMidWBufs) * kMidWVec + wave * 64) * 16;
+        lds_dma16(wsrc + (size_t)ks * 64, base);
+        if (n_w == 2) lds_dma16(wsrc + ((size_t)8 * a.ks_total + ks) * 64, base + (unsigned)(8 * 64) * 16);
+    };
+
+    f32x4 acc[kMidWTiles][RT];               // [feature tile of 16][row tile]: lane (c, g) holds features 4g..4g+3 of row c
+#pragma unroll
+    for (int i = 0; i < kMidWTiles; ++i)
+#pragma unroll
+        for (int t = 0; t < RT; ++t) acc[i][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int woff = kMidXBufs * kMidXVec + lane;                          // + W buffer + i * 64
+    const int xoff = wave * 64 + lane;                                     // + X buffer + t * 512
+
+    copy_w(0); copy_w(1); copy_w(2);
+    copy_x(0); copy_w(3);
+    copy_x(1); copy_w(4);
+    const int n_newer = my_tiles + 2 * n_w;  // issued after X(s): W(s+3), X(s+1), W(s+4)
+    int bx = 0, bw = 0;
+    for (int s = 0; s < n_stages; ++s) {
+        wait_vm_at_most(n_newer);
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        copy_x(s + 2);
+        copy_w(s + 5);
+        const u32x4 *xb = mid_lds + bx * kMidXVec, *wb = mid_lds + bw * kMidWVec;
+        bx = bx == kMidXBufs - 1 ? 0 : bx + 1;
+        bw = bw == kMidWBufs - 1 ? 0 : bw + 1;
+        if (my_tiles > 0) {
+            // tiles 0 and 1 unconditionally (a wavefront with one tile computes it twice and stores it once), tile 2
+            // where it exists: one uniform branch per k-step
+            bf16x8 xf[RT], wf[kMidWTiles];
+            xf[0] = __builtin_bit_cast(bf16x8, xb[xoff]);
+            xf[1] = __builtin_bit_cast(bf16x8, xb[xoff + (my_tiles > 1 ? 512 : 0)]);
+#pragma unroll
+            for (int i = 0; i < kMidWTiles; ++i) wf[i] = __builtin_bit_cast(bf16x8, wb[woff + i * 64]);
+            if (my_tiles == 3) xf[2] = __builtin_bit_cast(bf16x8, xb[xoff + 1024]);
+#pragma unroll
+            for (int i = 0; i < kMidWTiles; ++i)
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+                    acc[i][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[i], xf[t], acc[i][t], 0, 0, 0);
+            if (my_tiles == 3) {
+#pragma unroll
+                for (int i = 0; i < kMidWTiles; ++i)
+                    acc[i][2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[i], xf[2], acc[i][2], 0, 0, 0);
+            }
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    if (my_tiles == 0) return;
+
+    const int c = lane & 15, g = lane >> 4;
+#pragma unroll
+    for (int t = 0; t < RT; ++t) {
+        const int m = (wave + 8 * t) * 16 + c;
+        if (t >= my_tiles || m >= a.M) continue;
+        if constexpr (EPI == EPI_F32) {
+            float *out = (float *)a.out + (size_t)m * a.ld_out;
+#pragma unroll
+            for (int i = 0; i < kMidWTiles; ++i) {
+                const int n = nb * 160 + i * 16 + 4 * g;
+                if (n < a.N) *(f32x4 *)(out + n) = acc[i][t];
+            }
+        } else {
+            uint16_t *out = (uint16_t *)a.out;
+#pragma unroll
+            for (int i = 0; i < kMidWTiles / 2; ++i) {      // tile 2i = gate, tile 2i + 1 = up of features f..f+15
+                const int f = nb * 80 + i * 16 + 4 * g;
+                if (f < a.ld_out) {
+                    float r[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float gt = acc[2 * i][t][e];
+                        r[e] = gt / (1.0f + __expf(-gt)) * acc[2 * i + 1][t][e];
+                    }
+                    *(uint2 *)(out + frag_offset(m, f, a.mt_total)) =
+                        make_uint2(pack_bf16x2(r[0], r[1]), pack_bf16x2(r[2], r[3]));
+                }
+            }
+        }
+    }
+}
+
 // One thread per 16-byte lane slot of the packed matrix.
 __global__ void pack_rows_kernel(const uint16_t *__restrict__ src, int n_rows, int K, uint16_t *__restrict__ dst,
                                  int ks_total, int dst_row0, int interleave16, int which) {
@@ -607,11 +723,18 @@ int launch_mid(const GemmArgs &a, GemmEpilogue epi, hipStream_t stream) {
                                    kMidLdsBytes));
         SR_HIP(hipFuncSetAttribute((const void *)gemm_mid_kernel<EPI_SWIGLU>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                    kMidLdsBytes));
+        SR_HIP(hipFuncSetAttribute((const void *)gemm_mid16_kernel<EPI_F32>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   kMidLdsBytes));
+        SR_HIP(hipFuncSetAttribute((const void *)gemm_mid16_kernel<EPI_SWIGLU>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   kMidLdsBytes));
         attr_set = true;
     }
     if (a.M > 512 || a.splits != 1 || a.ks_total < 1 || round_up(a.M, 64) > a.mt_total * 16) return SR_E_ARG;
     dim3 grid((unsigned)ceil_div(a.N, 160)), block(kMidThreads);
-    if (epi == EPI_F32) gemm_mid_kernel<EPI_F32><<<grid, block, kMidLdsBytes, stream>>>(a);
+    if (a.M > 256 && a.M <= 384) {           // 17 .. 24 row tiles: three per wavefront, dealt out round robin
+        if (epi == EPI_F32) gemm_mid16_kernel<EPI_F32><<<grid, block, kMidLdsBytes, stream>>>(a);
+        else gemm_mid16_kernel<EPI_SWIGLU><<<grid, block, kMidLdsBytes, stream>>>(a);
+    } else if (epi == EPI_F32) gemm_mid_kernel<EPI_F32><<<grid, block, kMidLdsBytes, stream>>>(a);
     else gemm_mid_kernel<EPI_SWIGLU><<<grid, block, kMidLdsBytes, stream>>>(a);
     SR_HIP(hipGetLastError());
     return SR_OK;
