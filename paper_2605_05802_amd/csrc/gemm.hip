@@ -770,6 +770,27 @@ int launch_gemm(const GemmArgs &a, GemmEpilogue epi, hipStream_t stream) {
             // N of a few thousand only if the last round of workgroups is not mostly empty.
             const bool fills = tiles256 * 8 >= ceil_div(tiles256, 256) * 256 * 7;      // >= 87.5 % of the slots used
             if (a.N >= 16384 || (a.N >= 2048 && fills)) return launch_tiles256(a, epi, stream);
+            // Otherwise whole rounds of large tiles over the first column blocks and small tiles over the rest, where
+            // that is cheaper than small tiles throughout.  Measured at 8192 and 5120 rows, in units of one small tile
+            // among thousands: a round of large tiles costs 810; a launch of up to 256 small tiles (one per CU) 500, of
+            // up to 512 (two per CU) 1100.  QKV at 8192 rows: two rounds and 256 small tiles, 253 against 275 us; at 5120
+            // rows every thin projection is cheaper on small tiles alone.
+            if (a.N >= 2048 && mb256 <= 256) {
+                const int cols_per_round = 256 / mb256;
+                const int rounds_a = nb256 / cols_per_round;
+                const int c0 = rounds_a * cols_per_round * 256;
+                if (rounds_a > 0 && c0 < a.N) {
+                    const long long rest = (long long)m_blocks * ceil_div(a.N - c0, 128);
+                    const long long cost_mix = (long long)rounds_a * 810 + (rest <= 256 ? 500 : rest < 1100 ? 1100 : rest);
+                    const long long cost128 = (long long)m_blocks * ceil_div(a.N, 128);
+                    if (cost_mix < cost128) {
+                        GemmArgs first = a;
+                        first.N = c0;
+                        SR_TRY(launch_tiles256(first, epi, stream));
+                        return launch_tiles128(columns_from(a, epi, c0), epi, stream);
+                    }
+                }
+            }
             return launch_tiles128(a, epi, stream);
         }
         // A few hundred rows against a wide matrix (gate|up, LM head): every row in one workgroup of 160 features
